@@ -1,0 +1,156 @@
+/*
+ * cmn.h — C-ABI of libcmn: the per-iteration gradient aggregation + update of
+ * synchronous data-parallel training on one MI355X (gfx950).
+ *
+ * What is computed (ChainerMN paper, Section 2.3, "Allreduce" and
+ * "optimization" steps of an iteration; Section 3.3, the multi-node optimizer
+ * that exchanges gradients and then runs the wrapped optimizer; Section 2.1,
+ * the update rule):  K worker replicas each hold one gradient tensor per
+ * parameter tensor.  The step forms the element-wise average over the K
+ * replicas and updates the single shared copy of parameters with it.
+ * All K replicas' gradients are resident on the one GPU; the K-way reduction is
+ * the arithmetic every rank of an allreduce performs on its share.
+ *
+ * The order of the K-term float32 sum is fixed and part of the contract:
+ * the tightly packed concatenation of all tensors (length N) is cut into
+ * n_chunks equal chunks (each rounded up to align_bytes; only [N, L) is
+ * padding), and element i of chunk c is summed as
+ *     ((g[r0] + g[r1]) + g[r2]) + ... ,   r_j = (s + j) mod K,
+ * with s = c mod K if ring_rotate (the order an ascending-rank ring
+ * reduce-scatter produces) or s = 0 otherwise.
+ *
+ * Conventions for every function:
+ *  - returns CMN_OK (0) or a negative cmn_status; never throws, never aborts;
+ *  - pointers marked "host" are host memory read during the call only;
+ *    pointers marked "device" are device memory owned by the caller, which must
+ *    stay valid until the work queued on `stream` has finished;
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *    kernel entry points only enqueue work and do not synchronise;
+ *  - the library never allocates or frees device memory;
+ *  - a plan may be used by one host thread at a time;
+ *  - gradients are read-only; parameters and velocities are updated in place;
+ *    parameters, velocities, mean gradients and all sums are float32;
+ *  - no tensor may overlap another, except that mean_grad_ptrs[t] may equal
+ *    replica 0's gradient tensor grad_ptrs[t] when grad_dtype is CMN_F32.
+ */
+#ifndef CMN_H_
+#define CMN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cmn_plan cmn_plan; /* opaque; host memory owned by the library */
+
+enum cmn_status {
+    CMN_OK = 0,
+    CMN_EINVAL = -1,   /* an argument is out of range                              */
+    CMN_ENULL = -2,    /* a required pointer is NULL                                */
+    CMN_ESIZE = -3,    /* a size exceeds what the library supports                  */
+    CMN_EALIGN = -4,   /* a buffer that must be aligned is not                      */
+    CMN_EUNBOUND = -5, /* a kernel entry point was called before cmn_plan_bind      */
+    CMN_EHIP = -6,     /* the HIP runtime reported an error                         */
+    CMN_ENOMEM = -7    /* host memory could not be obtained                         */
+};
+
+enum cmn_dtype {
+    CMN_F32 = 0, /* gradients stored as IEEE binary32 */
+    CMN_F16 = 1  /* gradients stored as IEEE binary16, decoded exactly and summed in binary32 */
+};
+
+/* One unit of work of the tensor-space kernels (cmn_momentum_sgd, cmn_allreduce_step):
+ * `len` consecutive elements of tensor `tensor` starting at element `e0`, all inside
+ * one ring chunk whose sum starts at replica `start_rank`.  head_* is the number of
+ * leading elements handled one by one before the first 16-byte aligned vector of every
+ * stream the kernel touches, or -1 when the tensor's streams have no common alignment
+ * and the whole tile is processed element by element.  Exposed for inspection only. */
+typedef struct cmn_tile {
+    int64_t e0;
+    int32_t len;
+    int32_t tensor;
+    int32_t start_rank;
+    int32_t head_step;      /* cmn_allreduce_step without mean-gradient output */
+    int32_t head_step_mean; /* cmn_allreduce_step with mean-gradient output    */
+    int32_t head_sgd;       /* cmn_momentum_sgd                                 */
+} cmn_tile;
+
+/* Create a plan for `n_tensors` tensors of numel[t] >= 0 elements (host array, copied),
+ * K >= 1 replicas, n_chunks >= 1 ring chunks, align_bytes a power of two that is a
+ * multiple of 16 (256 in every published workload), grad_dtype a cmn_dtype, and
+ * ring_rotate 0 or 1.  n_tensors may be 0 and tensors may be empty.  Pure host work.
+ * Errors: CMN_ENULL (out, or numel with n_tensors > 0), CMN_EINVAL, CMN_ESIZE
+ * (n_tensors or K above the supported maximum, or sizes that overflow), CMN_ENOMEM. */
+int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel /* host [T] */, int K,
+                    int n_chunks, int align_bytes, int grad_dtype, int ring_rotate);
+
+/* Free the plan's host memory.  NULL is accepted.  Device buffers are the caller's. */
+int cmn_plan_destroy(cmn_plan *plan);
+
+int64_t cmn_plan_total_elems(const cmn_plan *plan);  /* N = sum of numel; -1 if plan is NULL      */
+int64_t cmn_plan_padded_elems(const cmn_plan *plan); /* L = n_chunks * chunk_elems                */
+int64_t cmn_plan_chunk_elems(const cmn_plan *plan);  /* roundup(ceil(N / n_chunks), align_bytes)  */
+int64_t cmn_plan_tile_count(const cmn_plan *plan);   /* number of cmn_tile work units             */
+size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_bind needs (>= 256) */
+
+/* Pure host: compute the work-unit table that cmn_plan_bind would upload for these
+ * pointer arrays (same meaning as in cmn_plan_bind; addresses are only inspected,
+ * never dereferenced) into tiles[0 .. cmn_plan_tile_count).  For tests and tooling. */
+int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, void *const *param_ptrs,
+                            void *const *vel_ptrs, void *const *mean_grad_ptrs, cmn_tile *tiles /* host */);
+
+/* Bind device tensors to the plan and upload the plan's tables into `dev_workspace`
+ * (device, 256-byte aligned, cmn_plan_workspace_bytes long; must outlive all later
+ * calls on this plan).  grad_ptrs is a host array of K*T device pointers, replica-major
+ * (grad_ptrs[k*T + t], element type grad_dtype, numel[t] elements, aligned to the
+ * element size); param_ptrs / vel_ptrs / mean_grad_ptrs are host arrays of T device
+ * float32 pointers (4-byte aligned).  Any of the four arrays may be NULL (param_ptrs and
+ * vel_ptrs only together); an entry point that needs an array that was not bound returns
+ * CMN_EUNBOUND: cmn_pack needs gradients, cmn_scale_unpack mean gradients,
+ * cmn_momentum_sgd mean gradients + parameters + velocities, cmn_allreduce_step gradients
+ * + parameters + velocities (+ mean gradients if asked to write them).  Pointers of empty
+ * tensors are ignored.  The call waits for `stream` before it returns.  May be
+ * repeated to rebind.  Errors: CMN_ENULL, CMN_EALIGN, CMN_EHIP. */
+int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_ptrs /* host [K*T] */,
+                  void *const *param_ptrs /* host [T] */, void *const *vel_ptrs /* host [T] */,
+                  void *const *mean_grad_ptrs /* host [T] or NULL */, void *stream);
+
+/* S1 pack.  For every replica k copy its T gradient tensors in list order, with no
+ * gaps, to packed[k*L .. k*L + N) and write zeros to packed[k*L + N .. (k+1)*L).
+ * packed: device, K*L elements of grad_dtype, 256-byte aligned.  Bit copy. */
+int cmn_pack(const cmn_plan *plan, void *packed /* device [K][L] */, void *stream);
+
+/* S2 ring-order reduction.  reduced[i] = fixed-order float32 sum over k of packed[k][i]
+ * (order defined at the top of this file).  packed as written by cmn_pack; reduced:
+ * device, L float32, 256-byte aligned, must not overlap packed.  Needs no bound tensors
+ * (but the plan must have been bound, for a uniform rule). */
+int cmn_ring_reduce(const cmn_plan *plan, const void *packed /* device [K][L] */,
+                    float *reduced /* device [L] */, void *stream);
+
+/* S3 + S4 scale and unpack.  mean_grad[t][e] = reduced[off[t] + e] * (1.0f / (float)K)
+ * for every tensor; padding is dropped.  Needs mean_grad_ptrs bound. */
+int cmn_scale_unpack(const cmn_plan *plan, const float *reduced /* device [L] */, void *stream);
+
+/* S5 MomentumSGD on every element, reading the bound mean gradients g:
+ *     g' = g + wd * p   (skipped when wd == 0);   v = mu * v - lr * g';   p = p + v
+ * each operation rounded to float32 once (no fused multiply-add).  lr is the learning
+ * rate (written mu in the paper's Section 2.1), mu the momentum coefficient. */
+int cmn_momentum_sgd(const cmn_plan *plan, float lr, float mu, float wd, void *stream);
+
+/* S1..S5 fused into one kernel launch with no intermediate buffer: for every element
+ * read the K replicas' gradients in the fixed order, sum, multiply by 1.0f/(float)K,
+ * apply the MomentumSGD rule above to p and v in place, and, if write_mean_grad != 0,
+ * also store the mean gradient to the bound mean_grad_ptrs.  Results are identical,
+ * bit for bit, to cmn_pack -> cmn_ring_reduce -> cmn_scale_unpack -> cmn_momentum_sgd. */
+int cmn_allreduce_step(const cmn_plan *plan, float lr, float mu, float wd, int write_mean_grad,
+                       void *stream);
+
+/* Static, never NULL. */
+const char *cmn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CMN_H_ */

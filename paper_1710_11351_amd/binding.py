@@ -1,0 +1,264 @@
+"""ctypes binding of libcmn.so: argument marshalling only.
+
+Module-level functions carry the names of the C entry points declared in
+``include/cmn.h``; ``Plan`` bundles a plan handle with the device workspace and
+the tensors it was bound to (so they stay alive).  PyTorch is used for device
+memory and stream handles, nothing else: every step runs in the HIP kernels.
+There is no fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcmn.so")
+
+CMN_OK, CMN_EINVAL, CMN_ENULL, CMN_ESIZE, CMN_EALIGN, CMN_EUNBOUND, CMN_EHIP, CMN_ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
+CMN_F32, CMN_F16 = 0, 1
+_DT = {"f32": CMN_F32, "f16": CMN_F16, CMN_F32: CMN_F32, CMN_F16: CMN_F16}
+
+
+class cmn_tile(ctypes.Structure):
+    _fields_ = [("e0", ctypes.c_int64), ("len", ctypes.c_int32), ("tensor", ctypes.c_int32),
+                ("start_rank", ctypes.c_int32), ("head_step", ctypes.c_int32),
+                ("head_step_mean", ctypes.c_int32), ("head_sgd", ctypes.c_int32)]
+
+
+TILE_DTYPE = np.dtype([("e0", "<i8"), ("len", "<i4"), ("tensor", "<i4"), ("start_rank", "<i4"),
+                       ("head_step", "<i4"), ("head_step_mean", "<i4"), ("head_sgd", "<i4")])
+
+
+class CmnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {cmn_strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcmn.so (built in-tree by ``paper_1710_11351_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no CPU or PyTorch fallback for the HIP path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64p, vpp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_void_p)
+    L.cmn_plan_create.restype = ctypes.c_int
+    L.cmn_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, ctypes.c_int, ctypes.c_int,
+                                  ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    L.cmn_plan_destroy.restype = ctypes.c_int
+    L.cmn_plan_destroy.argtypes = [vp]
+    for name in ("cmn_plan_total_elems", "cmn_plan_padded_elems", "cmn_plan_chunk_elems", "cmn_plan_tile_count"):
+        getattr(L, name).restype = ctypes.c_int64
+        getattr(L, name).argtypes = [vp]
+    L.cmn_plan_workspace_bytes.restype = ctypes.c_size_t
+    L.cmn_plan_workspace_bytes.argtypes = [vp]
+    L.cmn_plan_describe_tiles.restype = ctypes.c_int
+    L.cmn_plan_describe_tiles.argtypes = [vp, vpp, vpp, vpp, vpp, ctypes.POINTER(cmn_tile)]
+    L.cmn_plan_bind.restype = ctypes.c_int
+    L.cmn_plan_bind.argtypes = [vp, vp, vpp, vpp, vpp, vpp, vp]
+    L.cmn_pack.restype = ctypes.c_int
+    L.cmn_pack.argtypes = [vp, vp, vp]
+    L.cmn_ring_reduce.restype = ctypes.c_int
+    L.cmn_ring_reduce.argtypes = [vp, vp, vp, vp]
+    L.cmn_scale_unpack.restype = ctypes.c_int
+    L.cmn_scale_unpack.argtypes = [vp, vp, vp]
+    L.cmn_momentum_sgd.restype = ctypes.c_int
+    L.cmn_momentum_sgd.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp]
+    L.cmn_allreduce_step.restype = ctypes.c_int
+    L.cmn_allreduce_step.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int, vp]
+    L.cmn_strerror.restype = ctypes.c_char_p
+    L.cmn_strerror.argtypes = [ctypes.c_int]
+    _lib = L
+    return L
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _addr(x) -> Optional[int]:
+    """Device/host address of a tensor-like, or an int / None passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _ptr_array(ptrs: Optional[Sequence]):
+    if ptrs is None:
+        return None
+    arr = (ctypes.c_void_p * max(1, len(ptrs)))()
+    for i, p in enumerate(ptrs):
+        arr[i] = _addr(p)
+    return arr
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream)
+
+
+# ------------------------------------------------------------------ C entry points, same names
+def cmn_strerror(status: int) -> str:
+    return lib().cmn_strerror(int(status)).decode()
+
+
+def cmn_plan_create(numel: Sequence[int], K: int, n_chunks: int, align_bytes: int = 256, grad_dtype=CMN_F32,
+                    ring_rotate: int = 1):
+    """Returns (status, handle)."""
+    arr = np.ascontiguousarray(numel, dtype=np.int64)
+    h = ctypes.c_void_p()
+    rc = lib().cmn_plan_create(ctypes.byref(h), len(arr), arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                               int(K), int(n_chunks), int(align_bytes), int(_DT.get(grad_dtype, grad_dtype)),
+                               int(ring_rotate))
+    return rc, h
+
+
+def cmn_plan_destroy(h) -> int:
+    return lib().cmn_plan_destroy(h)
+
+
+def cmn_plan_total_elems(h) -> int:
+    return lib().cmn_plan_total_elems(h)
+
+
+def cmn_plan_padded_elems(h) -> int:
+    return lib().cmn_plan_padded_elems(h)
+
+
+def cmn_plan_chunk_elems(h) -> int:
+    return lib().cmn_plan_chunk_elems(h)
+
+
+def cmn_plan_tile_count(h) -> int:
+    return lib().cmn_plan_tile_count(h)
+
+
+def cmn_plan_workspace_bytes(h) -> int:
+    return lib().cmn_plan_workspace_bytes(h)
+
+
+def cmn_plan_describe_tiles(h, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs):
+    """Returns (status, numpy structured array of tiles).  Pointers are ints or tensors."""
+    n = max(0, cmn_plan_tile_count(h))
+    out = np.zeros(n, dtype=TILE_DTYPE)
+    rc = lib().cmn_plan_describe_tiles(h, _ptr_array(grad_ptrs), _ptr_array(param_ptrs), _ptr_array(vel_ptrs),
+                                       _ptr_array(mean_grad_ptrs),
+                                       out.ctypes.data_as(ctypes.POINTER(cmn_tile)) if n else None)
+    return rc, out
+
+
+def cmn_plan_bind(h, dev_workspace, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, stream=None) -> int:
+    return lib().cmn_plan_bind(h, _addr(dev_workspace), _ptr_array(grad_ptrs), _ptr_array(param_ptrs),
+                               _ptr_array(vel_ptrs), _ptr_array(mean_grad_ptrs), _stream(stream))
+
+
+def cmn_pack(h, packed, stream=None) -> int:
+    return lib().cmn_pack(h, _addr(packed), _stream(stream))
+
+
+def cmn_ring_reduce(h, packed, reduced, stream=None) -> int:
+    return lib().cmn_ring_reduce(h, _addr(packed), _addr(reduced), _stream(stream))
+
+
+def cmn_scale_unpack(h, reduced, stream=None) -> int:
+    return lib().cmn_scale_unpack(h, _addr(reduced), _stream(stream))
+
+
+def cmn_momentum_sgd(h, lr: float, mu: float, wd: float, stream=None) -> int:
+    return lib().cmn_momentum_sgd(h, lr, mu, wd, _stream(stream))
+
+
+def cmn_allreduce_step(h, lr: float, mu: float, wd: float, write_mean_grad: bool = False, stream=None) -> int:
+    return lib().cmn_allreduce_step(h, lr, mu, wd, int(bool(write_mean_grad)), _stream(stream))
+
+
+# ------------------------------------------------------------------ convenience wrapper
+def _check(rc: int, where: str) -> None:
+    if rc != CMN_OK:
+        raise CmnError(rc, where)
+
+
+class Plan:
+    """A plan handle plus the device workspace and bound tensors it refers to."""
+
+    def __init__(self, numel: Sequence[int], K: int, n_chunks: int, align_bytes: int = 256, grad_dtype="f32",
+                 ring_rotate: int = 1):
+        rc, self.h = cmn_plan_create(numel, K, n_chunks, align_bytes, grad_dtype, ring_rotate)
+        _check(rc, "cmn_plan_create")
+        self.numel = [int(n) for n in numel]
+        self.T, self.K, self.C = len(self.numel), int(K), int(n_chunks)
+        self.grad_dtype = _DT[grad_dtype]
+        self.N = cmn_plan_total_elems(self.h)
+        self.L = cmn_plan_padded_elems(self.h)
+        self.chunk_elems = cmn_plan_chunk_elems(self.h)
+        self.tile_count = cmn_plan_tile_count(self.h)
+        self.workspace_bytes = cmn_plan_workspace_bytes(self.h)
+        self._keep = None
+
+    def close(self) -> None:
+        if getattr(self, "h", None) is not None:
+            cmn_plan_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        self.close()
+
+    def bind(self, grads=None, params=None, vels=None, mean_grads=None, stream=None) -> None:
+        """grads[k][t], params[t], vels[t], mean_grads[t]: CUDA tensors (any may be None)."""
+        import torch
+        ws = torch.empty(self.workspace_bytes, dtype=torch.uint8, device="cuda")
+        flat = None if grads is None else [g for row in grads for g in row]
+        if grads is not None:
+            assert len(grads) == self.K and all(len(r) == self.T for r in grads)
+        _check(cmn_plan_bind(self.h, ws, flat, params, vels, mean_grads, stream), "cmn_plan_bind")
+        self._keep = (ws, grads, params, vels, mean_grads)
+
+    def pack(self, packed, stream=None) -> None:
+        _check(cmn_pack(self.h, packed, stream), "cmn_pack")
+
+    def ring_reduce(self, packed, reduced, stream=None) -> None:
+        _check(cmn_ring_reduce(self.h, packed, reduced, stream), "cmn_ring_reduce")
+
+    def scale_unpack(self, reduced, stream=None) -> None:
+        _check(cmn_scale_unpack(self.h, reduced, stream), "cmn_scale_unpack")
+
+    def momentum_sgd(self, lr, mu, wd, stream=None) -> None:
+        _check(cmn_momentum_sgd(self.h, lr, mu, wd, stream), "cmn_momentum_sgd")
+
+    def allreduce_step(self, lr, mu, wd, write_mean_grad=False, stream=None) -> None:
+        _check(cmn_allreduce_step(self.h, lr, mu, wd, write_mean_grad, stream), "cmn_allreduce_step")
+
+
+# ------------------------------------------------------------------ device-memory plumbing for callers
+def upload_tensors(arrays: Sequence[np.ndarray], misalign_elems: int = 0) -> List:
+    """Each host array becomes its own device allocation (so that packing is a real
+    gather).  ``misalign_elems`` > 0 returns views starting that many elements into a
+    slightly larger allocation, to exercise unaligned base pointers."""
+    import torch
+    out = []
+    for a in arrays:
+        src = torch.from_numpy(np.ascontiguousarray(a))
+        if misalign_elems:
+            buf = torch.empty(src.numel() + misalign_elems, dtype=src.dtype, device="cuda")
+            view = buf[misalign_elems:]
+            view.copy_(src)
+            out.append(view)
+        else:
+            out.append(src.to("cuda"))
+    return out
+
+
+def download_tensors(tensors: Sequence) -> List[np.ndarray]:
+    return [t.detach().cpu().numpy() for t in tensors]

@@ -1,0 +1,73 @@
+// Device-side helpers shared by the kernels: 16-byte vector access, exact
+// decoding of stored gradients to float32, and the element-wise arithmetic of
+// the scale and MomentumSGD steps.  Every float operation rounds once: the
+// translation units are built with contraction off and the pragma repeats it.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "../../include/cmn.h"
+
+#pragma clang fp contract(off)
+
+namespace cmn {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// Storage traits of the gradient element type.
+template <int DT> struct GradT;
+
+template <> struct GradT<CMN_F32> {
+    using elem = float;
+    using raw = f32x4;                 // one 16-byte load
+    static constexpr int VEC = 4;      // elements per 16-byte vector
+    static __device__ __forceinline__ void accumulate(float (&acc)[4], const raw &r) {
+        acc[0] = acc[0] + r.x; acc[1] = acc[1] + r.y; acc[2] = acc[2] + r.z; acc[3] = acc[3] + r.w;
+    }
+    static __device__ __forceinline__ float decode(elem x) { return x; }
+};
+
+template <> struct GradT<CMN_F16> {
+    using elem = _Float16;
+    using raw = f16x8;
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ void accumulate(float (&acc)[8], const raw &r) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = acc[i] + static_cast<float>(r[i]);  // exact widening
+    }
+    static __device__ __forceinline__ float decode(elem x) { return static_cast<float>(x); }
+};
+
+template <typename V>
+__device__ __forceinline__ V load_vec(const void *p) {
+    return *reinterpret_cast<const V *>(p);
+}
+
+// The K-term sum starts from -0.0f because x + (-0.0f) == x for every x, signed
+// zeros included, so the first addition reproduces the first gradient exactly.
+__device__ __forceinline__ constexpr float sum_identity() { return -0.0f; }
+
+// Replica visited at position j of the fold that starts at replica s.
+__device__ __forceinline__ int ring_rank(int s, int j, int K) {
+    const int r = s + j;
+    return r >= K ? r - K : r;
+}
+
+// MomentumSGD on one element; gbar is the averaged gradient.
+__device__ __forceinline__ void sgd_update(float gbar, float &p, float &v, float lr, float mu, float wd) {
+    float g = gbar;
+    if (wd != 0.0f) {
+        const float d = wd * p;
+        g = g + d;
+    }
+    const float t1 = mu * v;
+    const float t2 = lr * g;
+    v = t1 - t2;
+    p = p + v;
+}
+
+}  // namespace cmn

@@ -1,0 +1,261 @@
+// Host side of libcmn: plan creation, geometry of the packed index space, the
+// work-unit (tile) table of the tensor-space kernels, and binding of device
+// tensors.  The geometry follows the contract stated at the top of cmn.h.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "plan.hpp"
+
+namespace cmn {
+
+static size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
+
+static WorkspaceLayout make_layout(int T, int K, int64_t n_tiles) {
+    WorkspaceLayout w;
+    size_t o = 0;
+    w.off_table = o;  o = round256(o + sizeof(int64_t) * (size_t(T) + 1));
+    w.grad_rows = o;  o = round256(o + sizeof(void *) * size_t(T) * size_t(K));
+    w.grad_cols = o;  o = round256(o + sizeof(void *) * size_t(T) * size_t(K));
+    w.param_ptrs = o; o = round256(o + sizeof(void *) * size_t(T));
+    w.vel_ptrs = o;   o = round256(o + sizeof(void *) * size_t(T));
+    w.mean_ptrs = o;  o = round256(o + sizeof(void *) * size_t(T));
+    w.tiles = o;      o = round256(o + sizeof(cmn_tile) * size_t(n_tiles));
+    w.total = o < 256 ? 256 : o;
+    return w;
+}
+
+// Walk the tiles in table order: tensors in list order, each tensor cut at ring-chunk
+// edges (in packed coordinates) and at multiples of tile_elems (in tensor coordinates).
+template <typename F>
+static int64_t for_each_tile(const cmn_plan &p, F &&emit) {
+    int64_t count = 0;
+    if (p.chunk_elems == 0) return 0;
+    for (int t = 0; t < p.T; ++t) {
+        const int64_t n = p.numel[t], o = p.off[t];
+        int64_t e = 0;
+        while (e < n) {
+            const int64_t c = (o + e) / p.chunk_elems;
+            int64_t end = (c + 1) * p.chunk_elems - o;          // chunk edge, tensor coordinates
+            if (end > n) end = n;
+            const int64_t tile_end = (e / p.tile_elems + 1) * p.tile_elems;
+            if (end > tile_end) end = tile_end;
+            emit(t, e, int32_t(end - e), p.ring_rotate ? int32_t(c % p.K) : 0);
+            ++count;
+            e = end;
+        }
+    }
+    return count;
+}
+
+// Number of leading elements before element index 0 of a tensor reaches a 16-byte
+// boundary on every stream, or -1 if the streams disagree.  `vec` is the vector width
+// in elements of the narrowest stream (4 for float32, 8 for binary16 gradients).
+static int common_head(const void *const *g, int n_g, int g_elem_bytes, int vec, const void *const *f32,
+                       int n_f32) {
+    int a = -1;
+    for (int i = 0; i < n_g; ++i) {
+        const uintptr_t idx = reinterpret_cast<uintptr_t>(g[i]) / unsigned(g_elem_bytes);
+        const int ai = int((vec - int(idx % unsigned(vec))) % vec);
+        if (a < 0) a = ai;
+        else if (a != ai) return -1;
+    }
+    for (int i = 0; i < n_f32; ++i) {
+        const uintptr_t idx = reinterpret_cast<uintptr_t>(f32[i]) / 4u;
+        if (a < 0) a = int((vec - int(idx % unsigned(vec))) % vec);
+        else if ((idx + unsigned(a)) % 4u != 0) return -1;
+    }
+    return a;
+}
+
+void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *param_ptrs,
+                 void *const *vel_ptrs, void *const *mean_ptrs, cmn_tile *out) {
+    const int vec = vec_elems(p.dtype), geb = elem_bytes(p.dtype);
+    std::vector<int> h_step(p.T, -1), h_step_mean(p.T, -1), h_sgd(p.T, -1);
+    std::vector<const void *> g(p.K);
+    for (int t = 0; t < p.T; ++t) {
+        if (p.numel[t] == 0) continue;
+        const void *f32[3];
+        if (grad_ptrs && param_ptrs && vel_ptrs) {
+            for (int k = 0; k < p.K; ++k) g[k] = grad_ptrs[size_t(k) * p.T + t];
+            f32[0] = param_ptrs[t]; f32[1] = vel_ptrs[t];
+            h_step[t] = common_head(g.data(), p.K, geb, vec, f32, 2);
+            if (mean_ptrs) {
+                f32[2] = mean_ptrs[t];
+                h_step_mean[t] = common_head(g.data(), p.K, geb, vec, f32, 3);
+            }
+        }
+        if (mean_ptrs && param_ptrs && vel_ptrs) {
+            f32[0] = mean_ptrs[t]; f32[1] = param_ptrs[t]; f32[2] = vel_ptrs[t];
+            h_sgd[t] = common_head(nullptr, 0, 4, 4, f32, 3);
+        }
+    }
+    int64_t i = 0;
+    for_each_tile(p, [&](int t, int64_t e0, int32_t len, int32_t start) {
+        cmn_tile &tl = out[i++];
+        tl.e0 = e0; tl.len = len; tl.tensor = t; tl.start_rank = start;
+        auto head = [&](int a, int v) { return a < 0 ? -1 : int32_t(((a - e0) % v + v) % v); };
+        tl.head_step = head(h_step[t], vec);
+        tl.head_step_mean = head(h_step_mean[t], vec);
+        tl.head_sgd = head(h_sgd[t], 4);
+    });
+}
+
+int check_launch(const cmn_plan *p) {
+    if (!p) return CMN_ENULL;
+    if (!p->bound) return CMN_EUNBOUND;
+    return CMN_OK;
+}
+
+}  // namespace cmn
+
+using namespace cmn;
+
+extern "C" {
+
+int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, int n_chunks,
+                    int align_bytes, int grad_dtype, int ring_rotate) {
+    if (!out) return CMN_ENULL;
+    *out = nullptr;
+    if (n_tensors < 0 || K < 1 || n_chunks < 1) return CMN_EINVAL;
+    if (n_tensors > 0 && !numel) return CMN_ENULL;
+    if (grad_dtype != CMN_F32 && grad_dtype != CMN_F16) return CMN_EINVAL;
+    if (ring_rotate != 0 && ring_rotate != 1) return CMN_EINVAL;
+    if (align_bytes < 16 || (align_bytes & (align_bytes - 1)) != 0) return CMN_EINVAL;
+    if (n_tensors > kMaxTensors || K > kMaxReplicas || align_bytes > (1 << 20)) return CMN_ESIZE;
+
+    cmn_plan *p = new (std::nothrow) cmn_plan;
+    if (!p) return CMN_ENOMEM;
+    try {
+        p->T = n_tensors; p->K = K; p->C = n_chunks; p->align_bytes = align_bytes;
+        p->dtype = grad_dtype; p->ring_rotate = ring_rotate;
+        p->numel.assign(numel, numel + n_tensors);
+        p->off.assign(size_t(n_tensors) + 1, 0);
+    } catch (...) { delete p; return CMN_ENOMEM; }
+
+    const int64_t kMaxElems = int64_t(1) << 46;  // keeps every byte offset far inside int64
+    for (int t = 0; t < n_tensors; ++t) {
+        if (numel[t] < 0) { delete p; return CMN_EINVAL; }
+        if (numel[t] > kMaxElems || p->off[t] > kMaxElems) { delete p; return CMN_ESIZE; }
+        p->off[t + 1] = p->off[t] + numel[t];
+    }
+    p->N = p->off[n_tensors];
+    const int64_t A = align_bytes / elem_bytes(grad_dtype);
+    const int64_t per = (p->N + n_chunks - 1) / n_chunks;
+    p->chunk_elems = (per + A - 1) / A * A;
+    p->L = p->chunk_elems * n_chunks;
+    if (p->L > kMaxElems || p->L * K > (int64_t(1) << 50)) { delete p; return CMN_ESIZE; }
+
+    int iters = kTileIters;
+    if (const char *s = std::getenv("CMN_TILE_ITERS")) {  // tuning knob for experiments
+        const int v = std::atoi(s);
+        if (v >= 1 && v <= 64) iters = v;
+    }
+    p->tile_elems = kBlock * vec_elems(grad_dtype) * iters;
+    p->n_tiles = for_each_tile(*p, [](int, int64_t, int32_t, int32_t) {});
+    if (p->n_tiles > (int64_t(1) << 31) - 1) { delete p; return CMN_ESIZE; }
+    p->ws = make_layout(p->T, p->K, p->n_tiles);
+    *out = p;
+    return CMN_OK;
+}
+
+int cmn_plan_destroy(cmn_plan *plan) {
+    delete plan;
+    return CMN_OK;
+}
+
+int64_t cmn_plan_total_elems(const cmn_plan *p) { return p ? p->N : -1; }
+int64_t cmn_plan_padded_elems(const cmn_plan *p) { return p ? p->L : -1; }
+int64_t cmn_plan_chunk_elems(const cmn_plan *p) { return p ? p->chunk_elems : -1; }
+int64_t cmn_plan_tile_count(const cmn_plan *p) { return p ? p->n_tiles : -1; }
+size_t cmn_plan_workspace_bytes(const cmn_plan *p) { return p ? p->ws.total : 0; }
+
+static int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows, unsigned elem_bytes) {
+    for (int r = 0; r < rows; ++r)
+        for (int t = 0; t < p->T; ++t) {
+            if (p->numel[t] == 0) continue;
+            const void *q = ptrs[size_t(r) * p->T + t];
+            if (!q) return CMN_ENULL;
+            if (reinterpret_cast<uintptr_t>(q) % elem_bytes) return CMN_EALIGN;
+        }
+    return CMN_OK;
+}
+
+int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, void *const *param_ptrs,
+                            void *const *vel_ptrs, void *const *mean_grad_ptrs, cmn_tile *tiles) {
+    if (!plan || (!tiles && plan->n_tiles > 0)) return CMN_ENULL;
+    int rc;
+    if (grad_ptrs && (rc = check_ptr_array(plan, grad_ptrs, plan->K, elem_bytes(plan->dtype)))) return rc;
+    if (param_ptrs && (rc = check_ptr_array(plan, param_ptrs, 1, 4))) return rc;
+    if (vel_ptrs && (rc = check_ptr_array(plan, vel_ptrs, 1, 4))) return rc;
+    if (mean_grad_ptrs && (rc = check_ptr_array(plan, mean_grad_ptrs, 1, 4))) return rc;
+    try {
+        build_tiles(*plan, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, tiles);
+    } catch (...) { return CMN_ENOMEM; }
+    return CMN_OK;
+}
+
+int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_ptrs, void *const *param_ptrs,
+                  void *const *vel_ptrs, void *const *mean_grad_ptrs, void *stream) {
+    if (!plan || !dev_workspace) return CMN_ENULL;
+    if (reinterpret_cast<uintptr_t>(dev_workspace) % 256) return CMN_EALIGN;
+    if ((param_ptrs == nullptr) != (vel_ptrs == nullptr)) return CMN_ENULL;
+    cmn_plan *p = plan;
+    int rc;
+    if (grad_ptrs && (rc = check_ptr_array(p, grad_ptrs, p->K, elem_bytes(p->dtype)))) return rc;
+    if (param_ptrs && (rc = check_ptr_array(p, param_ptrs, 1, 4))) return rc;
+    if (vel_ptrs && (rc = check_ptr_array(p, vel_ptrs, 1, 4))) return rc;
+    if (mean_grad_ptrs && (rc = check_ptr_array(p, mean_grad_ptrs, 1, 4))) return rc;
+
+    p->bound = false;
+    try {
+        p->staging.assign(p->ws.total, 0);
+    } catch (...) { return CMN_ENOMEM; }
+    unsigned char *img = p->staging.data();
+    std::memcpy(img + p->ws.off_table, p->off.data(), sizeof(int64_t) * (size_t(p->T) + 1));
+    const size_t T = size_t(p->T), K = size_t(p->K);
+    if (grad_ptrs) {
+        auto **rows = reinterpret_cast<const void **>(img + p->ws.grad_rows);
+        auto **cols = reinterpret_cast<const void **>(img + p->ws.grad_cols);
+        for (size_t k = 0; k < K; ++k)
+            for (size_t t = 0; t < T; ++t) {
+                rows[k * T + t] = grad_ptrs[k * T + t];
+                cols[t * K + k] = grad_ptrs[k * T + t];
+            }
+    }
+    if (param_ptrs) std::memcpy(img + p->ws.param_ptrs, param_ptrs, sizeof(void *) * T);
+    if (vel_ptrs) std::memcpy(img + p->ws.vel_ptrs, vel_ptrs, sizeof(void *) * T);
+    if (mean_grad_ptrs) std::memcpy(img + p->ws.mean_ptrs, mean_grad_ptrs, sizeof(void *) * T);
+    try {
+        build_tiles(*p, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs,
+                    reinterpret_cast<cmn_tile *>(img + p->ws.tiles));
+    } catch (...) { return CMN_ENOMEM; }
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(dev_workspace, img, p->ws.total, hipMemcpyHostToDevice, s) != hipSuccess) return CMN_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return CMN_EHIP;
+    p->dev_ws = static_cast<char *>(dev_workspace);
+    p->have_grads = grad_ptrs != nullptr;
+    p->have_opt = param_ptrs != nullptr;
+    p->have_mean = mean_grad_ptrs != nullptr;
+    p->bound = true;
+    return CMN_OK;
+}
+
+const char *cmn_strerror(int status) {
+    switch (status) {
+        case CMN_OK: return "ok";
+        case CMN_EINVAL: return "invalid argument";
+        case CMN_ENULL: return "required pointer is NULL";
+        case CMN_ESIZE: return "size exceeds the supported maximum";
+        case CMN_EALIGN: return "buffer is not sufficiently aligned";
+        case CMN_EUNBOUND: return "plan is not bound to the tensors this call needs";
+        case CMN_EHIP: return "HIP runtime error";
+        case CMN_ENOMEM: return "out of host memory";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

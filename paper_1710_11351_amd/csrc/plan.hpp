@@ -1,0 +1,65 @@
+// Internal: the plan object behind the opaque cmn_plan handle and the layout of
+// its device-side tables.  Host code only; the kernels receive plain pointers.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/cmn.h"
+
+namespace cmn {
+
+constexpr int kMaxTensors = 1 << 20;
+constexpr int kMaxReplicas = 4096;
+constexpr int kBlock = 256;  // threads per workgroup of every kernel (4 wavefronts)
+
+// Elements of one cmn_tile at most: kBlock threads x one 16-byte vector x kTileIters.
+constexpr int kTileIters = 2;
+
+inline int elem_bytes(int dtype) { return dtype == CMN_F16 ? 2 : 4; }
+inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }
+
+// Byte offsets of the tables inside the caller's device workspace (each 256-aligned).
+struct WorkspaceLayout {
+    size_t off_table = 0;    // int64 [T+1]   prefix sums of numel
+    size_t grad_rows = 0;    // void* [K][T]  replica-major (rows go to LDS in pack)
+    size_t grad_cols = 0;    // void* [T][K]  tensor-major (one tile reads K neighbours)
+    size_t param_ptrs = 0;   // float* [T]
+    size_t vel_ptrs = 0;     // float* [T]
+    size_t mean_ptrs = 0;    // float* [T]
+    size_t tiles = 0;        // cmn_tile [n_tiles]
+    size_t total = 0;
+};
+
+}  // namespace cmn
+
+struct cmn_plan {
+    int T = 0, K = 1, C = 1, align_bytes = 256, dtype = CMN_F32, ring_rotate = 1;
+    int tile_elems = 0;
+    std::vector<int64_t> numel;  // [T]
+    std::vector<int64_t> off;    // [T+1]
+    int64_t N = 0, chunk_elems = 0, L = 0, n_tiles = 0;
+    cmn::WorkspaceLayout ws;
+
+    // state set by cmn_plan_bind
+    bool bound = false, have_grads = false, have_opt = false, have_mean = false;
+    char *dev_ws = nullptr;
+    std::vector<unsigned char> staging;  // host image of the workspace
+};
+
+namespace cmn {
+
+// Fills out[0..n_tiles) for the given pointer arrays (may be null: heads become -1).
+void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *param_ptrs,
+                 void *const *vel_ptrs, void *const *mean_ptrs, cmn_tile *out);
+
+// Shared argument checks of the kernel entry points.
+int check_launch(const cmn_plan *p);
+
+template <typename T>
+inline T *ws_ptr(const cmn_plan *p, size_t byte_off) {
+    return reinterpret_cast<T *>(p->dev_ws + byte_off);
+}
+
+}  // namespace cmn

@@ -1,0 +1,80 @@
+// cmn_ring_reduce: K packed replica buffers [K][L] -> one float32 sum [L].
+// A workgroup owns one tile of one ring chunk, so the fold order (which replica
+// is read first) is uniform over the workgroup and every output vector is
+// produced once by one thread: K streaming reads, one streaming write.
+#include <hip/hip_runtime.h>
+
+#include "device_util.hpp"
+#include "plan.hpp"
+
+#pragma clang fp contract(off)
+
+namespace cmn {
+
+constexpr int kReduceIters = 2;  // 16-byte vectors per thread per stream
+
+template <int DT, int U>
+__global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__ packed,
+                                                        float *__restrict__ reduced, long long L,
+                                                        long long chunk_elems, int tiles_per_chunk, int K,
+                                                        int ring_rotate) {
+    using G = GradT<DT>;
+    using elem = typename G::elem;
+    using raw = typename G::raw;
+    constexpr int VEC = G::VEC;
+    constexpr int TILE = kBlock * VEC * kReduceIters;
+
+    const int c = blockIdx.x / tiles_per_chunk;
+    const int tile = blockIdx.x - c * tiles_per_chunk;
+    const int s = ring_rotate ? c % K : 0;
+    const long long chunk_begin = c * chunk_elems;
+    const int in_chunk = int(min((long long)TILE, chunk_elems - (long long)tile * TILE));
+    const elem *src = static_cast<const elem *>(packed) + chunk_begin + (long long)tile * TILE;
+    float *dst = reduced + chunk_begin + (long long)tile * TILE;
+
+    // chunk_elems is a multiple of the alignment, hence of VEC: no ragged vectors
+    for (int e = threadIdx.x * VEC; e < in_chunk; e += kBlock * VEC) {
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
+        int j = 0;
+        for (; j + U <= K; j += U) {
+            raw g[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) g[u] = load_vec<raw>(src + (long long)ring_rank(s, j + u, K) * L + e);
+#pragma unroll
+            for (int u = 0; u < U; ++u) G::accumulate(acc, g[u]);
+        }
+        for (; j < K; ++j) G::accumulate(acc, load_vec<raw>(src + (long long)ring_rank(s, j, K) * L + e));
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            f32x4 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = acc[4 * q + i];
+            *reinterpret_cast<f32x4 *>(dst + e + 4 * q) = o;
+        }
+    }
+}
+
+}  // namespace cmn
+
+using namespace cmn;
+
+extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *reduced, void *stream) {
+    if (!plan) return CMN_ENULL;
+    if (plan->L == 0) return CMN_OK;
+    if (!packed || !reduced) return CMN_ENULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(reduced) % 256) return CMN_EALIGN;
+    const int tile = kBlock * vec_elems(plan->dtype) * kReduceIters;
+    const long long tpc = (plan->chunk_elems + tile - 1) / tile;
+    if (tpc * plan->C > 0x7fffffffLL) return CMN_ESIZE;
+    const dim3 grid(unsigned(tpc * plan->C));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (plan->dtype == CMN_F32)
+        hipLaunchKernelGGL((k_ring_reduce<CMN_F32, 8>), grid, dim3(kBlock), 0, s, packed, reduced,
+                           (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate);
+    else
+        hipLaunchKernelGGL((k_ring_reduce<CMN_F16, 8>), grid, dim3(kBlock), 0, s, packed, reduced,
+                           (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate);
+    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+}

@@ -1,0 +1,142 @@
+"""Shared driver of the GPU parity tests: runs the oracle and the HIP path on the
+same seeded host arrays and compares every output the path produces."""
+import numpy as np
+
+import oracle
+from paper_1710_11351_amd import binding as B
+from paper_1710_11351_amd import workloads as wl
+
+
+def bits(a):
+    a = np.ascontiguousarray(a)
+    return a.view(np.uint16 if a.dtype == np.float16 else np.uint32)
+
+
+def assert_bit_equal(got, want, what):
+    got, want = np.asarray(got).reshape(-1), np.asarray(want).reshape(-1)
+    assert got.shape == want.shape, f"{what}: shape {got.shape} vs {want.shape}"
+    bad = np.nonzero(bits(got) != bits(want))[0]
+    if bad.size:
+        both_nan = np.isnan(got[bad]) & np.isnan(want[bad])
+        bad = bad[~both_nan]
+    assert bad.size == 0, (f"{what}: {bad.size} of {got.size} elements differ, first at {bad[:5]}: "
+                           f"got {got[bad[:5]]} want {want[bad[:5]]}")
+
+
+def assert_update_close(got, want, what, rel=1e-6):
+    """The stated bar for the optimizer outputs: |a-b| <= rel * max(|b|, rms(b)) per tensor."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    if want.size == 0:
+        return
+    rms = np.sqrt(np.mean(want ** 2))
+    err = np.abs(got - want) - rel * np.maximum(np.abs(want), rms)
+    assert np.all(err <= 0), f"{what}: exceeds {rel} relative by {err.max()}"
+
+
+class DeviceCase:
+    """Device tensors of one workload, each tensor its own allocation."""
+
+    def __init__(self, c: wl.Config, ring_rotate=1, misalign=0, with_mean=True):
+        import torch
+        self.c, self.torch = c, torch
+        self.np_g = np.float16 if c.grad_dtype == "f16" else np.float32
+        tg = torch.float16 if c.grad_dtype == "f16" else torch.float32
+        self.plan = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype, ring_rotate)
+
+        def alloc(dtype):
+            out = []
+            for n in c.numel:
+                buf = torch.zeros(n + misalign, dtype=dtype, device="cuda")
+                out.append(buf[misalign:])
+            return out
+
+        self.grads = [alloc(tg) for _ in range(c.K)]
+        self.p, self.v = alloc(torch.float32), alloc(torch.float32)
+        self.m = alloc(torch.float32) if with_mean else None
+        self.plan.bind(self.grads, self.p, self.v, self.m)
+
+    def set_state(self, p_host, v_host):
+        for d, h in zip(self.p, p_host):
+            d.copy_(self.torch.from_numpy(h))
+        for d, h in zip(self.v, v_host):
+            d.copy_(self.torch.from_numpy(h))
+
+    def set_grads(self, k, g_host):
+        for d, h in zip(self.grads[k], g_host):
+            d.copy_(self.torch.from_numpy(np.ascontiguousarray(h)))
+
+    def get(self, tensors):
+        self.torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in tensors]
+
+
+def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fused=True, check_packed=True):
+    """Oracle vs HIP on `steps` consecutive iterations with fresh gradients each."""
+    import torch
+    p_o = [x.copy() for x in wl.gen_params(c)]
+    v_o = [x.copy() for x in wl.gen_velocity(c)]
+    cases = {}
+    if fused:
+        cases["fused"] = DeviceCase(c, ring_rotate, misalign)
+    if staged:
+        cases["staged"] = DeviceCase(c, ring_rotate, misalign)
+    for dc in cases.values():
+        dc.set_state(p_o, v_o)
+    geo = oracle.Geometry(c.numel, c.n_chunks, c.align_bytes, c.grad_dtype)
+    if staged:
+        dc = cases["staged"]
+        tg = torch.float16 if c.grad_dtype == "f16" else torch.float32
+        packed = torch.full((c.K * geo.L + 64,), 7.0, dtype=tg, device="cuda")[: c.K * geo.L]
+        reduced = torch.full((geo.L + 64,), 7.0, dtype=torch.float32, device="cuda")[: geo.L]
+        assert dc.plan.L == geo.L
+
+    for step in range(steps):
+        grads = [wl.gen_grads(c, step, k) for k in range(c.K)]
+        for dc in cases.values():
+            for k in range(c.K):
+                dc.set_grads(k, grads[k])
+        # ---- oracle, step by step with intermediates
+        packed_o = [oracle.pack(geo, grads[k]) for k in range(c.K)]
+        total_o = oracle.direct_fold(geo, packed_o, ring_rotate)
+        mean_o = oracle.unpack(geo, oracle.scale(total_o, c.K))
+        for t in range(geo.T):
+            oracle.momentum_sgd(mean_o[t], p_o[t], v_o[t], c.lr, c.mu, c.wd)
+
+        if staged:
+            dc = cases["staged"]
+            dc.plan.pack(packed)
+            if check_packed:
+                torch.cuda.synchronize()
+                for k in range(c.K):
+                    assert_bit_equal(packed[k * geo.L:(k + 1) * geo.L].cpu().numpy(), packed_o[k],
+                                     f"step {step} packed[{k}]")
+            dc.plan.ring_reduce(packed, reduced)
+            torch.cuda.synchronize()
+            assert_bit_equal(reduced.cpu().numpy(), total_o, f"step {step} ring_reduce")
+            dc.plan.scale_unpack(reduced)
+            for t, (a, b) in enumerate(zip(dc.get(dc.m), mean_o)):
+                assert_bit_equal(a, b, f"step {step} staged mean_grad[{t}]")
+            dc.plan.momentum_sgd(c.lr, c.mu, c.wd)
+            _compare_state(dc, p_o, v_o, f"step {step} staged")
+        if fused:
+            dc = cases["fused"]
+            write_mean = step % 2 == 0
+            if write_mean:
+                for m in dc.m:
+                    m.fill_(-5.0)
+            dc.plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=write_mean)
+            _compare_state(dc, p_o, v_o, f"step {step} fused")
+            if write_mean:
+                for t, (a, b) in enumerate(zip(dc.get(dc.m), mean_o)):
+                    assert_bit_equal(a, b, f"step {step} fused mean_grad[{t}]")
+        del packed_o, total_o
+    return p_o, v_o
+
+
+def _compare_state(dc, p_o, v_o, what):
+    for t, (a, b) in enumerate(zip(dc.get(dc.p), p_o)):
+        assert_update_close(a, b, f"{what} p[{t}]")     # the stated bar
+        assert_bit_equal(a, b, f"{what} p[{t}]")        # what the kernels actually achieve
+    for t, (a, b) in enumerate(zip(dc.get(dc.v), v_o)):
+        assert_update_close(a, b, f"{what} v[{t}]")
+        assert_bit_equal(a, b, f"{what} v[{t}]")

@@ -1,0 +1,86 @@
+"""HIP path vs CPU oracle, element by element, through the C-ABI (needs the GPU)."""
+import numpy as np
+import pytest
+
+from paper_1710_11351_amd import workloads as wl
+from parity_util import run_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_mlp_k2():
+    run_parity(wl.config(1), steps=3)
+
+
+@pytest.mark.parametrize("rot", [0, 1])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_ragged_list_with_empty_tensors(dtype, rot):
+    # odd sizes, empty tensors, tiles and vectors that straddle tensor and chunk edges, K not a power of two
+    numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3]
+    c = wl.custom_config(numel, K=3, n_chunks=5, grad_dtype=dtype, cfg=91, wd=1e-3,
+                         outlier_frac=0.01 if dtype == "f16" else 0.0)
+    run_parity(c, steps=3, ring_rotate=rot)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("misalign", [1, 3])
+def test_unaligned_base_pointers(dtype, misalign):
+    c = wl.custom_config([1000, 4096, 37, 8192 + 5], K=4, n_chunks=4, grad_dtype=dtype, cfg=92)
+    run_parity(c, steps=2, misalign=misalign)
+
+
+def test_single_replica_is_the_plain_optimizer():
+    c = wl.custom_config([3000, 100], K=1, n_chunks=1, cfg=93)
+    run_parity(c, steps=2)
+
+
+def test_fewer_elements_than_chunks():
+    c = wl.custom_config([3, 2], K=4, n_chunks=8, cfg=94)     # most chunks are pure padding
+    run_parity(c, steps=2)
+
+
+def test_more_chunks_than_replicas_and_k7():
+    c = wl.custom_config([70000, 333], K=7, n_chunks=14, cfg=95)
+    run_parity(c, steps=2)
+
+
+def test_many_replicas_f16_k40():
+    c = wl.custom_config([20000, 1000, 24], K=40, n_chunks=40, grad_dtype="f16", cfg=96, outlier_frac=0.01)
+    run_parity(c, steps=2)
+
+
+def test_special_values_propagate():
+    import torch
+    from paper_1710_11351_amd import binding as B
+    n = 1024
+    plan = B.Plan([n], 2, 2)
+    a = np.zeros(n, np.float32); b = np.zeros(n, np.float32)
+    a[0], b[0] = np.inf, 1.0
+    a[1], b[1] = np.inf, -np.inf
+    a[2], b[2] = -0.0, -0.0
+    a[3], b[3] = 1e-45, 1e-45
+    a[4], b[4] = 1e-40, 2e-40
+    g = [[torch.from_numpy(a).cuda()], [torch.from_numpy(b).cuda()]]
+    p = [torch.zeros(n, device="cuda")]; v = [torch.zeros(n, device="cuda")]; m = [torch.ones(n, device="cuda")]
+    plan.bind(g, p, v, m)
+    plan.allreduce_step(1.0, 0.0, 0.0, write_mean_grad=True)
+    out = m[0].cpu().numpy()
+    assert out[0] == np.inf and np.isnan(out[1])
+    assert out[2] == 0 and np.signbit(out[2])
+    assert out[3] == np.float32(1e-45) and out[4] == (np.float32(1e-40) + np.float32(2e-40)) * np.float32(0.5)
+    assert not out[5:].any()
+
+
+def test_empty_plan_is_a_no_op():
+    from paper_1710_11351_amd import binding as B
+    plan = B.Plan([0, 0], 2, 2)
+    import torch
+    e = lambda: [torch.zeros(0, device="cuda") for _ in range(2)]
+    plan.bind([e(), e()], e(), e(), e())
+    plan.pack(None); plan.ring_reduce(None, None); plan.scale_unpack(None)
+    plan.momentum_sgd(.1, .9, 0.); plan.allreduce_step(.1, .9, 0., True)
+    torch.cuda.synchronize()
+
+
+def test_config2_resnet50_k4_full_size():
+    run_parity(wl.config(2), steps=3)

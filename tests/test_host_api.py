@@ -1,0 +1,171 @@
+"""Host-side tests of the C-ABI library: they need no GPU and launch nothing."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1710_11351_amd import binding as B
+from paper_1710_11351_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "cmn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(cmn_[a-z_]+)\s*\(", text)))
+    assert {"cmn_pack", "cmn_ring_reduce", "cmn_scale_unpack", "cmn_momentum_sgd", "cmn_allreduce_step",
+            "cmn_plan_create", "cmn_plan_bind", "cmn_plan_destroy", "cmn_strerror"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), f"libcmn.so does not export {n}"
+        assert hasattr(B, n), f"the Python binding has no function named {n}"
+
+
+def test_strerror_is_total():
+    for s in range(-9, 2):
+        assert isinstance(B.cmn_strerror(s), str) and B.cmn_strerror(s)
+    assert B.cmn_strerror(B.CMN_OK) == "ok"
+
+
+@pytest.mark.parametrize("args,status", [
+    (dict(numel=[4], K=0, n_chunks=1), B.CMN_EINVAL),
+    (dict(numel=[4], K=1, n_chunks=0), B.CMN_EINVAL),
+    (dict(numel=[4, -1], K=1, n_chunks=1), B.CMN_EINVAL),
+    (dict(numel=[4], K=1, n_chunks=1, align_bytes=48), B.CMN_EINVAL),
+    (dict(numel=[4], K=1, n_chunks=1, align_bytes=8), B.CMN_EINVAL),
+    (dict(numel=[4], K=1, n_chunks=1, grad_dtype=7), B.CMN_EINVAL),
+    (dict(numel=[4], K=1, n_chunks=1, ring_rotate=2), B.CMN_EINVAL),
+    (dict(numel=[4], K=5000, n_chunks=1), B.CMN_ESIZE),
+    (dict(numel=[1 << 50], K=1, n_chunks=1), B.CMN_ESIZE),
+])
+def test_plan_create_rejects(args, status):
+    rc, h = B.cmn_plan_create(**args)
+    assert rc == status and not h.value
+
+
+def test_null_arguments():
+    L = B.lib()
+    assert L.cmn_plan_create(None, 0, None, 1, 1, 256, 0, 1) == B.CMN_ENULL
+    import ctypes
+    h = ctypes.c_void_p()
+    assert L.cmn_plan_create(ctypes.byref(h), 2, None, 1, 1, 256, 0, 1) == B.CMN_ENULL
+    assert B.cmn_plan_total_elems(None) == -1 and B.cmn_plan_workspace_bytes(None) == 0
+    assert B.cmn_plan_destroy(None) == B.CMN_OK
+    for call in (lambda: B.cmn_pack(None, 256, 0), lambda: B.cmn_ring_reduce(None, 256, 512, 0),
+                 lambda: B.cmn_scale_unpack(None, 256, 0), lambda: B.cmn_momentum_sgd(None, .1, .9, 0., 0),
+                 lambda: B.cmn_allreduce_step(None, .1, .9, 0., False, 0)):
+        assert call() == B.CMN_ENULL
+
+
+def test_kernel_entry_points_refuse_an_unbound_plan():
+    p = B.Plan([100, 28], 2, 2)
+    assert B.cmn_pack(p.h, 256, 0) == B.CMN_EUNBOUND
+    assert B.cmn_scale_unpack(p.h, 256, 0) == B.CMN_EUNBOUND
+    assert B.cmn_momentum_sgd(p.h, .1, .9, 0., 0) == B.CMN_EUNBOUND
+    assert B.cmn_allreduce_step(p.h, .1, .9, 0., False, 0) == B.CMN_EUNBOUND
+    # argument checks of the one entry point that needs no binding
+    assert B.cmn_ring_reduce(p.h, None, 512, 0) == B.CMN_ENULL
+    assert B.cmn_ring_reduce(p.h, 260, 512, 0) == B.CMN_EALIGN
+    assert B.cmn_plan_bind(p.h, None, None, None, None, None, 0) == B.CMN_ENULL
+    assert B.cmn_plan_bind(p.h, 260, None, None, None, None, 0) == B.CMN_EALIGN
+    assert B.cmn_plan_bind(p.h, 256, None, [1024, 2048], None, None, 0) == B.CMN_ENULL   # p without v
+    assert B.cmn_plan_bind(p.h, 256, [1024, 0, 4096, 8192], None, None, None, 0) == B.CMN_ENULL
+    assert B.cmn_plan_bind(p.h, 256, None, [1024, 2050], [4096, 8192], None, 0) == B.CMN_EALIGN
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+@pytest.mark.parametrize("row", _rows("geometry.txt"), ids=lambda r: "cfg" + r[0])
+def test_plan_geometry_matches_hand_worked_table(row):
+    c = wl.config(int(row[0]))
+    p = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype)
+    assert (p.T, p.N, p.chunk_elems, p.L) == (int(row[2]), int(row[3]), int(row[6]), int(row[7]))
+    assert p.workspace_bytes % 256 == 0 and p.workspace_bytes >= 256
+
+
+def test_plan_geometry_agrees_with_oracle_on_random_lists():
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        T = int(rng.integers(0, 12))
+        numel = [int(x) for x in rng.choice([0, 1, 3, 63, 64, 65, 1000, 4097], T)]
+        C = int(rng.integers(1, 9))
+        dt = ["f32", "f16"][int(rng.integers(0, 2))]
+        align = int(rng.choice([16, 64, 256, 1024]))
+        p = B.Plan(numel, int(rng.integers(1, 9)), C, align, dt)
+        g = oracle.Geometry(numel, C, align, dt)
+        assert (p.N, p.chunk_elems, p.L) == (g.N, g.chunk_elems, g.L)
+
+
+def _fake_ptrs(numel, base, elem_bytes, misalign=0):
+    out, a = [], base
+    for n in numel:
+        out.append(a + misalign * elem_bytes if n else 0)
+        a += ((n * elem_bytes + 511) // 512 + 1) * 512
+    return out, a
+
+
+@pytest.mark.parametrize("dtype,rot", [("f32", 1), ("f32", 0), ("f16", 1)])
+def test_tile_table_covers_every_element_once_inside_one_chunk(dtype, rot):
+    numel = [5, 0, 5000, 1, 64, 12345, 7]
+    K, C = 3, 5
+    p = B.Plan(numel, K, C, 256, dtype, rot)
+    eb = 2 if dtype == "f16" else 4
+    vec = 16 // eb
+    base = 1 << 20
+    grads = []
+    for k in range(K):
+        g, base = _fake_ptrs(numel, base, eb)
+        grads += g
+    pp, base = _fake_ptrs(numel, base, 4)
+    vp, base = _fake_ptrs(numel, base, 4)
+    mp, base = _fake_ptrs(numel, base, 4)
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, grads, pp, vp, mp)
+    assert rc == B.CMN_OK and len(tiles) == p.tile_count
+    off = np.concatenate([[0], np.cumsum(numel)])
+    covered = {t: 0 for t in range(len(numel))}
+    for tl in tiles:
+        t, e0, ln = int(tl["tensor"]), int(tl["e0"]), int(tl["len"])
+        assert ln > 0 and covered[t] == e0            # in order, no gap, no overlap
+        covered[t] = e0 + ln
+        c_first, c_last = (off[t] + e0) // p.chunk_elems, (off[t] + e0 + ln - 1) // p.chunk_elems
+        assert c_first == c_last
+        assert int(tl["start_rank"]) == (c_first % K if rot else 0)
+        # all fake bases are 512-byte aligned, so the head only depends on e0
+        assert int(tl["head_step"]) == (-e0) % vec and int(tl["head_step_mean"]) == (-e0) % vec
+        assert int(tl["head_sgd"]) == (-e0) % 4
+    assert [covered[t] for t in range(len(numel))] == numel
+
+
+def test_tile_heads_follow_pointer_alignment():
+    numel = [1000]
+    p = B.Plan(numel, 2, 1)
+    a = 1 << 20
+    # both replicas, p and v start 3 elements past a 16-byte boundary: one leading element
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a + 12, 2 * a + 12], [3 * a + 12], [4 * a + 12], [5 * a + 12])
+    assert rc == 0 and [int(t["head_step"]) for t in tiles][0] == 1 and int(tiles[0]["head_sgd"]) == 1
+    # replicas disagree: no common alignment
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a + 12, 2 * a + 8], [3 * a + 12], [4 * a + 12], [5 * a + 12])
+    assert rc == 0 and int(tiles[0]["head_step"]) == -1 and int(tiles[0]["head_sgd"]) == 1
+    # mean gradient misaligned differently: only the variants that touch it lose the vector path
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a, 2 * a], [3 * a], [4 * a], [5 * a + 4])
+    assert rc == 0 and int(tiles[0]["head_step"]) == 0
+    assert int(tiles[0]["head_step_mean"]) == -1 and int(tiles[0]["head_sgd"]) == -1
+    # unbound arrays
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, None, None, None, None)
+    assert rc == 0 and int(tiles[0]["head_step"]) == -1
+    rc, _ = B.cmn_plan_describe_tiles(p.h, [a + 2, 2 * a], None, None, None)
+    assert rc == B.CMN_EALIGN
+
+
+def test_empty_plans():
+    for numel in ([], [0, 0]):
+        p = B.Plan(numel, 4, 4)
+        assert (p.N, p.L, p.chunk_elems, p.tile_count) == (0, 0, 0, 0)
+        assert p.workspace_bytes >= 256
