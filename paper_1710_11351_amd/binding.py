@@ -208,12 +208,15 @@ class Plan:
         self._keep = None
 
     def close(self) -> None:
-        if getattr(self, "h", None) is not None:
-            cmn_plan_destroy(self.h)
+        if getattr(self, "h", None) is not None and _lib is not None:
+            _lib.cmn_plan_destroy(self.h)
             self.h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:   # interpreter shutdown: globals may already be gone
+            pass
 
     def bind(self, grads=None, params=None, vels=None, mean_grads=None, stream=None) -> None:
         """grads[k][t], params[t], vels[t], mean_grads[t]: CUDA tensors (any may be None)."""

@@ -52,12 +52,12 @@ __global__ __launch_bounds__(kBlock) void k_allreduce_step(
             raw g[U];
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                g[u] = load_vec<raw>(static_cast<const elem *>(gcol[ring_rank(s, j + u, K)]) + tl.e0 + e);
+                g[u] = load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j + u, K)]) + tl.e0 + e);
 #pragma unroll
             for (int u = 0; u < U; ++u) G::accumulate(acc, g[u]);
         }
         for (; j < K; ++j) {
-            const raw g = load_vec<raw>(static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e);
+            const raw g = load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e);
             G::accumulate(acc, g);
         }
 
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void k_allreduce_step(
 
 template <int DT, bool WM>
 static void launch_step(const cmn_plan *p, float lr, float mu, float wd, hipStream_t s) {
-    constexpr int U = 8;
+    constexpr int U = 16;
     hipLaunchKernelGGL((k_allreduce_step<DT, U, WM>), dim3(unsigned(p->n_tiles)), dim3(kBlock), 0, s,
                        ws_ptr<const cmn_tile>(p, p->ws.tiles), ws_ptr<const void *const>(p, p->ws.grad_cols),
                        ws_ptr<float *const>(p, p->ws.param_ptrs), ws_ptr<float *const>(p, p->ws.vel_ptrs),

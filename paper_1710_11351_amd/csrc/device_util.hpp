@@ -47,6 +47,14 @@ __device__ __forceinline__ V load_vec(const void *p) {
     return *reinterpret_cast<const V *>(p);
 }
 
+// Load of data that is read exactly once per launch (gradients, packed buffers):
+// the non-temporal hint keeps it from displacing reusable lines in L2 and in the
+// memory-side cache, and measurably raises streaming read bandwidth on MI355X.
+template <typename V>
+__device__ __forceinline__ V load_stream(const void *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
+}
+
 // The K-term sum starts from -0.0f because x + (-0.0f) == x for every x, signed
 // zeros included, so the first addition reproduces the first gradient exactly.
 __device__ __forceinline__ constexpr float sum_identity() { return -0.0f; }

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kBlock) void k_pack(const long long *__restrict__ o
             if (t < 0 || i >= off(t + 1)) t = find_tensor(off, T, i);
             const elem *src = ptr(t) + (i - off(t));
             if (i + VEC <= off(t + 1) && (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
-                out = load_vec<raw>(src);
+                out = load_stream<raw>(src);
             } else {
                 int tt = t;
 #pragma unroll
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void k_scale_unpack(const long long *__rest
     for (int it = 0; it < kPackIters; ++it) {
         const long long i = tile_begin + (long long)(it * kBlock + threadIdx.x) * 4;
         if (i >= N) break;
-        f32x4 g = load_vec<f32x4>(reduced + i);          // i + 4 <= L: L is a multiple of 4
+        f32x4 g = load_stream<f32x4>(reduced + i);         // i + 4 <= L: L is a multiple of 4
 #pragma unroll
         for (int j = 0; j < 4; ++j) g[j] = g[j] * inv_k;
         if (t < 0 || i >= off(t + 1)) t = find_tensor(off, T, i);

@@ -15,7 +15,7 @@ constexpr int kMaxReplicas = 4096;
 constexpr int kBlock = 256;  // threads per workgroup of every kernel (4 wavefronts)
 
 // Elements of one cmn_tile at most: kBlock threads x one 16-byte vector x kTileIters.
-constexpr int kTileIters = 2;
+constexpr int kTileIters = 1;
 
 inline int elem_bytes(int dtype) { return dtype == CMN_F16 ? 2 : 4; }
 inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }

@@ -11,7 +11,7 @@
 
 namespace cmn {
 
-constexpr int kReduceIters = 2;  // 16-byte vectors per thread per stream
+constexpr int kReduceIters = 1;  // 16-byte vectors per thread per stream
 
 template <int DT, int U>
 __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__ packed,
@@ -41,11 +41,11 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
         for (; j + U <= K; j += U) {
             raw g[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) g[u] = load_vec<raw>(src + (long long)ring_rank(s, j + u, K) * L + e);
+            for (int u = 0; u < U; ++u) g[u] = load_stream<raw>(src + (long long)ring_rank(s, j + u, K) * L + e);
 #pragma unroll
             for (int u = 0; u < U; ++u) G::accumulate(acc, g[u]);
         }
-        for (; j < K; ++j) G::accumulate(acc, load_vec<raw>(src + (long long)ring_rank(s, j, K) * L + e));
+        for (; j < K; ++j) G::accumulate(acc, load_stream<raw>(src + (long long)ring_rank(s, j, K) * L + e));
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
             f32x4 o;
@@ -71,10 +71,10 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
     const dim3 grid(unsigned(tpc * plan->C));
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (plan->dtype == CMN_F32)
-        hipLaunchKernelGGL((k_ring_reduce<CMN_F32, 8>), grid, dim3(kBlock), 0, s, packed, reduced,
+        hipLaunchKernelGGL((k_ring_reduce<CMN_F32, 16>), grid, dim3(kBlock), 0, s, packed, reduced,
                            (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate);
     else
-        hipLaunchKernelGGL((k_ring_reduce<CMN_F16, 8>), grid, dim3(kBlock), 0, s, packed, reduced,
+        hipLaunchKernelGGL((k_ring_reduce<CMN_F16, 16>), grid, dim3(kBlock), 0, s, packed, reduced,
                            (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate);
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }
