@@ -23,8 +23,8 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 
 # HBM bytes per launch of the fused kernel at config 3 read by rocprofv3 --pmc
 # (FETCH_SIZE, WRITE_SIZE), scaled by the same counters' reading of a plain copy of
-# known size; None until measured.  Source: profiles/allreduce_step_resnet50_k32_pmc.txt
-MEASURED_TRAFFIC_BYTES = {3: None}
+# known size (scale 2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).  Source: profiles/allreduce_step_resnet50_k32_pmc.txt
+MEASURED_TRAFFIC_BYTES = {3: 3_683_500_000}
 
 
 def log(*a):
@@ -132,13 +132,18 @@ def main():
             log(f"[bench] {name}: {extra[name]['us']} us, {extra[name]['GBps']} GB/s effective")
         del packed, reduced
 
-    # a plain device copy of 2 GiB as the box's streaming ceiling (context only)
-    src = torch.empty(1 << 29, dtype=torch.float32, device="cuda")
-    dst = torch.empty_like(src)
-    pr, _, _ = time_launches(torch, lambda: dst.copy_(src), 10, 2)
-    copy_gbps = 2 * src.numel() * 4 / (float(np.mean(pr)) * 1e-3) / 1e9
-    log(f"[bench] plain 2 GiB device copy: {copy_gbps:.0f} GB/s (read+write)")
-    del src, dst
+    # A plain copy of known size through the library's own gather kernel (one tensor,
+    # one replica: cmn_pack degenerates to a 1 GiB -> 1 GiB copy).  It gives the box's
+    # copy rate as context and calibrates the rocprofv3 FETCH_SIZE / WRITE_SIZE counters.
+    cal_n = 1 << 28
+    src = torch.empty(cal_n, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty(cal_n, dtype=torch.float32, device="cuda")
+    cal = B.Plan([cal_n], 1, 1, 256, "f32")
+    cal.bind([[src]], None, None, None)
+    pr, _, _ = time_launches(torch, lambda: cal.pack(dst), 10, 2)
+    copy_gbps = 2 * cal_n * 4 / (float(np.mean(pr)) * 1e-3) / 1e9
+    log(f"[bench] calibration copy (cmn_pack, 1 GiB -> 1 GiB): {copy_gbps:.0f} GB/s (read+write)")
+    del src, dst, cal
 
     cpu = None
     if not args.no_cpu:
