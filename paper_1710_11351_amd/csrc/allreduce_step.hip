@@ -34,6 +34,9 @@ __global__ __launch_bounds__(kBlock) void k_allreduce_step(
     if (head < 0 || head > len) head = len;
     const int nvec = (len - head) / VEC;
     const int tail0 = head + nvec * VEC;
+    const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, unsigned(len) * 4u);
+    const __amdgpu_buffer_rsrc_t v_out = make_rsrc(v, unsigned(len) * 4u);
+    const __amdgpu_buffer_rsrc_t m_out = make_rsrc(m, WRITE_MEAN ? unsigned(len) * 4u : 0u);
 
     for (int vi = threadIdx.x; vi < nvec; vi += kBlock) {
         const unsigned e = unsigned(head + vi * VEC);
@@ -71,9 +74,9 @@ __global__ __launch_bounds__(kBlock) void k_allreduce_step(
                 sgd_update(gb[i], pi, vi2, lr, mu, wd);
                 pv[q][i] = pi; vv[q][i] = vi2;
             }
-            if (WRITE_MEAN) *reinterpret_cast<f32x4 *>(m + e + 4 * q) = gb;
-            *reinterpret_cast<f32x4 *>(v + e + 4 * q) = vv[q];
-            *reinterpret_cast<f32x4 *>(p + e + 4 * q) = pv[q];
+            if (WRITE_MEAN) store_through(m_out, (e + 4 * q) * 4u, gb);
+            store_through(v_out, (e + 4 * q) * 4u, vv[q]);
+            store_through(p_out, (e + 4 * q) * 4u, pv[q]);
         }
     }
 

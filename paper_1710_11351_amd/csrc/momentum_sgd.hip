@@ -24,6 +24,8 @@ __global__ __launch_bounds__(kBlock) void k_momentum_sgd(
     if (head < 0 || head > len) head = len;
     const int nvec = (len - head) / 4;
     const int tail0 = head + nvec * 4;
+    const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, unsigned(len) * 4u);
+    const __amdgpu_buffer_rsrc_t v_out = make_rsrc(v, unsigned(len) * 4u);
 
     for (int vi = threadIdx.x; vi < nvec; vi += kBlock) {
         const unsigned e = unsigned(head + vi * 4);
@@ -36,8 +38,8 @@ __global__ __launch_bounds__(kBlock) void k_momentum_sgd(
             sgd_update(gv[i], pi, vi2, lr, mu, wd);
             pv[i] = pi; vv[i] = vi2;
         }
-        *reinterpret_cast<f32x4 *>(v + e) = vv;
-        *reinterpret_cast<f32x4 *>(p + e) = pv;
+        store_through(v_out, e * 4u, vv);
+        store_through(p_out, e * 4u, pv);
     }
     const int n_single = head + (len - tail0);
     for (int i = threadIdx.x; i < n_single; i += kBlock) {

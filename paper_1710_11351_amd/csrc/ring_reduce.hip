@@ -31,6 +31,7 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
     const int in_chunk = int(min((long long)TILE, chunk_elems - (long long)tile * TILE));
     const elem *src = static_cast<const elem *>(packed) + chunk_begin + (long long)tile * TILE;
     float *dst = reduced + chunk_begin + (long long)tile * TILE;
+    const __amdgpu_buffer_rsrc_t out = make_rsrc(dst, unsigned(in_chunk) * 4u);
 
     // chunk_elems is a multiple of the alignment, hence of VEC: no ragged vectors
     for (int e = threadIdx.x * VEC; e < in_chunk; e += kBlock * VEC) {
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
             f32x4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = acc[4 * q + i];
-            *reinterpret_cast<f32x4 *>(dst + e + 4 * q) = o;
+            store_through(out, unsigned(e + 4 * q) * 4u, o);
         }
     }
 }
