@@ -84,3 +84,46 @@ def test_empty_plan_is_a_no_op():
 
 def test_config2_resnet50_k4_full_size():
     run_parity(wl.config(2), steps=3)
+
+
+# ---- the benchmark workloads at full size, in the launch configuration bench.py times ----
+def test_config3_resnet50_k32_full_size():
+    run_parity(wl.config(3), steps=3)
+
+
+def test_config4_resnet50_k128_f16_full_size():
+    run_parity(wl.config(4), steps=2)
+
+
+def test_config5_vgg16_k16_weight_decay_full_size():
+    run_parity(wl.config(5), steps=2)
+
+
+def test_f16_storage_within_2e3_of_unquantised_fp32():
+    """Config 4's value distribution (1 % of elements at 100x) on a smaller list: the mean gradient
+    from fp16-stored gradients stays within 2e-3 of the float64 mean b of the un-quantised fp32
+    draws, relative to max(|b|, mean_k |g_k|) element by element.  (Rounding to binary16 moves
+    each normal element by at most 2^-11 = 4.9e-4 of its magnitude and each subnormal by at most
+    2^-25, so the mean moves by at most 4.9e-4 * mean_k |g_k| + 3e-8: the bar has 4x headroom.)"""
+    import torch
+    from paper_1710_11351_amd import binding as B
+    from parity_util import gen_all_grads
+    import dataclasses
+    c4 = wl.config(4)
+    numel = [36864, 64, 64, 147456, 1000, 4096, 589824]
+    c = dataclasses.replace(wl.custom_config(numel, K=128, n_chunks=128, grad_dtype="f16", cfg=97,
+                                             grad_std=c4.grad_std, outlier_frac=c4.outlier_frac), outlier_scale=c4.outlier_scale)
+    g16 = gen_all_grads(c, 0)
+    g32 = gen_all_grads(c, 0, unquantised=True)
+    d_g = [B.upload_tensors(g) for g in g16]
+    d_p = B.upload_tensors(wl.gen_params(c)); d_v = B.upload_tensors(wl.gen_velocity(c))
+    d_m = [torch.zeros(n, device="cuda") for n in numel]
+    plan = B.Plan(numel, c.K, c.n_chunks, 256, "f16")
+    plan.bind(d_g, d_p, d_v, d_m)
+    plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=True)
+    got = B.download_tensors(d_m)
+    for t in range(len(numel)):
+        st = np.stack([g[t].astype(np.float64) for g in g32])
+        want, mag = st.mean(axis=0), np.abs(st).mean(axis=0)
+        assert np.all(np.abs(got[t] - want) <= 2e-3 * np.maximum(np.abs(want), mag)), f"tensor {t}"
+        assert np.max(np.abs(got[t] - want)) > 0     # the quantisation is really there
