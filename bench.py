@@ -94,13 +94,15 @@ def main():
     host_grads = []                                 # kept for the CPU leg when it fits
     keep_host = not args.no_cpu
     d_g = []
-    for k in range(c.K):
-        g = wl.gen_grads(c, 0, k)
-        d_g.append(B.upload_tensors(g))             # every tensor its own allocation
-        if keep_host:
-            host_grads.append(g)
-        if k % 8 == 7:
-            log(f"[bench] generated + uploaded replica {k + 1}/{c.K} ({time.time() - t0:.1f}s)")
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=8) as ex:   # numpy's generators release the GIL
+        for k0 in range(0, c.K, 8):
+            batch = list(ex.map(lambda k: wl.gen_grads(c, 0, k), range(k0, min(c.K, k0 + 8))))
+            for g in batch:
+                d_g.append(B.upload_tensors(g))     # every tensor its own allocation
+                if keep_host:
+                    host_grads.append(g)
+            log(f"[bench] generated + uploaded replicas {len(d_g)}/{c.K} ({time.time() - t0:.1f}s)")
     p_h, v_h = wl.gen_params(c), wl.gen_velocity(c)
     d_p, d_v = B.upload_tensors(p_h), B.upload_tensors(v_h)
     d_m = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in c.numel]
