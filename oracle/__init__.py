@@ -38,7 +38,8 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        # the mutation test points this at a deliberately broken copy to show the pins catch it
+        L = ctypes.CDLL(os.environ.get("CMN_ORACLE_LIB_FOR_MUTATION_TEST") or build())
         i64p = ctypes.POINTER(ctypes.c_int64)
         vpp = ctypes.POINTER(ctypes.c_void_p)
         fp = ctypes.POINTER(ctypes.c_float)
