@@ -27,7 +27,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc: one rounding per operation, OpenMP over chunks."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
-               "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB]
+               "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", _LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -62,6 +62,14 @@ def lib() -> ctypes.CDLL:
         L.orc_momentum_sgd.restype = None
         L.orc_momentum_sgd.argtypes = [ctypes.c_int64, fp, fp, fp, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_float]
+        L.orc_float_to_half_bits.restype = ctypes.c_uint16
+        L.orc_float_to_half_bits.argtypes = [ctypes.c_float]
+        L.orc_float_to_half_array.restype = None
+        L.orc_float_to_half_array.argtypes = [ctypes.c_int64, fp, ctypes.c_void_p]
+        L.orc_adam_lr.restype = ctypes.c_float
+        L.orc_adam_lr.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int]
+        L.orc_adam.restype = None
+        L.orc_adam.argtypes = [ctypes.c_int64, fp, fp, fp, fp] + [ctypes.c_float] * 5
         L.orc_max_threads.restype = ctypes.c_int
         L.orc_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -173,6 +181,35 @@ def momentum_sgd(g: np.ndarray, p: np.ndarray, v: np.ndarray, lr: float, mu: flo
     """S5 on one tensor, p and v updated in place."""
     assert g.size == p.size == v.size
     lib().orc_momentum_sgd(g.size, _fp(g), _fp(p), _fp(v), float(lr), float(mu), float(wd))
+
+
+def float_to_half(a: np.ndarray) -> np.ndarray:
+    """binary32 -> binary16, round to nearest even, through the oracle's own encoder."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.uint16)
+    lib().orc_float_to_half_array(a.size, _fp(a.reshape(-1)), out.ctypes.data)
+    return out.view(np.float16)
+
+
+def adam_lr(alpha: float, beta1: float, beta2: float, t: int) -> float:
+    return float(lib().orc_adam_lr(alpha, beta1, beta2, int(t)))
+
+
+def adam(g: np.ndarray, p: np.ndarray, m: np.ndarray, v: np.ndarray, alpha: float, beta1: float, beta2: float,
+         eps: float, wd: float, t: int) -> None:
+    """Adam on one tensor at iteration t (1-based); p, m, v updated in place."""
+    assert g.size == p.size == m.size == v.size
+    lib().orc_adam(g.size, _fp(g), _fp(p), _fp(m), _fp(v), adam_lr(alpha, beta1, beta2, t), float(beta1),
+                   float(beta2), float(eps), float(wd))
+
+
+def mean_gradients(grads: Sequence[Sequence[np.ndarray]], numel: Sequence[int], n_chunks: int, *, dtype="f32",
+                   align_bytes: int = 256, ring_rotate: int = 1) -> List[np.ndarray]:
+    """S1..S4: pack, fold, scale, unpack -> the T averaged gradient tensors (float32)."""
+    K = len(grads)
+    geo = Geometry(numel, n_chunks, align_bytes, dtype)
+    packed = [pack(geo, grads[k]) for k in range(K)]
+    return unpack(geo, scale(direct_fold(geo, packed, ring_rotate), K))
 
 
 def allreduce_step(grads: Sequence[Sequence[np.ndarray]], params: List[np.ndarray], vels: List[np.ndarray],

@@ -200,6 +200,80 @@ void orc_momentum_sgd(int64_t n, const float *g, float *p, float *v, float lr, f
     }
 }
 
+/* ---- binary32 -> binary16, round to nearest even, bit level ----------------------
+ * Used where the averaged gradient is handed back to replicas that store binary16. */
+uint16_t orc_float_to_half_bits(float f)
+{
+    uint32_t x;
+    memcpy(&x, &f, 4);
+    uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    uint32_t exp8 = (x >> 23) & 0xffu;
+    uint32_t man23 = x & 0x7fffffu;
+    if (exp8 == 255) return (uint16_t)(sign | 0x7c00u | (man23 ? 0x200u | (man23 >> 13) : 0u)); /* Inf, quiet NaN */
+    int e = (int)exp8 - 127 + 15;               /* exponent in binary16's bias */
+    if (e >= 31) return (uint16_t)(sign | 0x7c00u);                  /* too large: infinity */
+    if (e <= 0) {                               /* result is subnormal or zero */
+        if (e < -10) return sign;               /* below half of the smallest subnormal */
+        uint32_t m = man23 | 0x800000u;         /* make the leading one explicit */
+        int shift = 14 - e;                     /* 14 .. 24 */
+        uint32_t q = m >> shift, rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
+        if (rem > half || (rem == half && (q & 1u))) ++q;            /* nearest, ties to even */
+        return (uint16_t)(sign | q);            /* a carry lands on the smallest normal: correct */
+    }
+    uint32_t h = ((uint32_t)e << 10) | (man23 >> 13);
+    uint32_t rem = man23 & 0x1fffu;
+    if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;          /* carry may reach infinity: correct */
+    return (uint16_t)(sign | h);
+}
+
+void orc_float_to_half_array(int64_t n, const float *in, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_float_to_half_bits(in[i]);
+}
+
+/* ---- Adam (Kingma & Ba) in the arrangement with the bias corrections folded into
+ * the step size; the paper's Listing 1 wraps this optimizer (Section 3.3):
+ *     g' = g + wd * p                  (only when wd != 0)
+ *     m  = m + (1 - beta1) * (g' - m)
+ *     v  = v + (1 - beta2) * (g'*g' - v)
+ *     p  = p - lr_t * m / (sqrt(v) + eps),   lr_t = alpha * sqrt(1 - beta2^t) / (1 - beta1^t)
+ * Every operation is rounded to float32 once; sqrt and the division are correctly rounded.
+ * lr_t is formed in double from the float32 hyper-parameters and rounded once. */
+#include <math.h>
+float orc_adam_lr(float alpha, float beta1, float beta2, int t)
+{
+    double b1 = 1.0 - pow((double)beta1, (double)t);
+    double b2 = 1.0 - pow((double)beta2, (double)t);
+    return (float)((double)alpha * sqrt(b2) / b1);
+}
+
+void orc_adam(int64_t n, const float *g, float *p, float *m, float *v, float lr_t, float beta1, float beta2,
+              float eps, float wd)
+{
+    float c1 = 1.0f - beta1, c2 = 1.0f - beta2;
+    for (int64_t i = 0; i < n; ++i) {
+        float gi = g[i];
+        if (wd != 0.0f) {
+            float dec = wd * p[i];
+            gi = gi + dec;
+        }
+        float t1 = gi - m[i];
+        float t2 = c1 * t1;
+        float mn = m[i] + t2;
+        float t3 = gi * gi;
+        float t4 = t3 - v[i];
+        float t5 = c2 * t4;
+        float vn = v[i] + t5;
+        float s = sqrtf(vn);
+        float den = s + eps;
+        float q = mn / den;
+        float u = lr_t * q;
+        m[i] = mn;
+        v[i] = vn;
+        p[i] = p[i] - u;
+    }
+}
+
 int orc_max_threads(void);
 #ifdef _OPENMP
 #include <omp.h>

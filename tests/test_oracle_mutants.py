@@ -34,6 +34,19 @@ MUTANTS = [
     ("half_subnormal_scale", "(float)man10 * 0x1p-24f", "(float)man10 * 0x1p-25f"),
     ("half_drops_sign_of_subnormal", "bits |= sign << 31;", "(void)sign;"),
     ("half_mantissa_shift", "| (man10 << 13); /* rebias", "| (man10 << 12); /* rebias"),
+    ("encode_truncates", "if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;", "(void)rem;"),
+    ("encode_ties_away", "(rem == 0x1000u && (h & 1u))) ++h;", "(rem == 0x1000u)) ++h;"),
+    ("encode_subnormal_truncates", "if (rem > half || (rem == half && (q & 1u))) ++q;", "(void)rem; (void)half;"),
+    ("encode_flushes_subnormals", "if (e < -10) return sign;", "if (e <= 0) return sign;"),
+    ("encode_saturates_instead_of_inf", "if (e >= 31) return (uint16_t)(sign | 0x7c00u);", "if (e >= 31) return (uint16_t)(sign | 0x7bffu);"),
+    ("adam_first_moment_no_decay", "float mn = m[i] + t2;", "float mn = m[i] + t1;"),
+    ("adam_second_moment_uses_g", "float t3 = gi * gi;", "float t3 = gi;"),
+    ("adam_eps_inside_sqrt", "float s = sqrtf(vn);\n        float den = s + eps;", "float s = sqrtf(vn + eps);\n        float den = s;"),
+    ("adam_ascends", "p[i] = p[i] - u;", "p[i] = p[i] + u;"),
+    ("adam_uses_old_moment", "float q = mn / den;", "float q = m[i] / den;"),
+    ("adam_lr_without_second_correction", "return (float)((double)alpha * sqrt(b2) / b1);", "return (float)((double)alpha / b1);"),
+    ("adam_lr_corrections_swapped", "return (float)((double)alpha * sqrt(b2) / b1);", "return (float)((double)alpha * sqrt(b1) / b2);"),
+    ("adam_decay_dropped", "gi = gi + dec;", "(void)dec;"),
 ]
 
 
@@ -50,7 +63,7 @@ def test_pins_kill_mutant(tmp_path, name, old, new):
     lib = tmp_path / "libmut.so"
     src.write_text(text.replace(old, new))
     subprocess.run(["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared",
-                    "-fPIC", str(src), "-o", str(lib)], check=True)
+                    "-fPIC", str(src), "-o", str(lib), "-lm"], check=True)
     env = dict(os.environ, CMN_ORACLE_LIB_FOR_MUTATION_TEST=str(lib))
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
                         os.path.join(ROOT, "tests", "test_oracle_pins.py")], cwd=ROOT, env=env,

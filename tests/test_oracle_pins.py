@@ -342,3 +342,114 @@ def test_config1_end_to_end_against_float64():
             p64[t] = p64[t] + v64[t]
             rms = np.sqrt(np.mean(p64[t] ** 2))
             assert np.all(np.abs(p[t] - p64[t]) <= 1e-6 * np.maximum(np.abs(p64[t]), rms))
+
+
+# ------------------------------------------------------------------ binary32 -> binary16 encode
+def test_half_encode_against_numpy_on_edges_and_random_patterns():
+    rng = np.random.default_rng(12)
+    edges = []
+    for h in range(0, 65536, 1):                       # every binary16 value, its neighbours and midpoints
+        edges.append(h)
+    hv = np.array(edges, dtype=np.uint16).view(np.float16).astype(np.float32)
+    hv = hv[np.isfinite(hv)]
+    nxt = np.nextafter(hv, np.float32(np.inf)); prv = np.nextafter(hv, np.float32(-np.inf))
+    mid = ((hv.astype(np.float64) + np.sort(hv).astype(np.float64)[np.searchsorted(np.sort(hv), hv, side="right").clip(0, hv.size - 1)]) / 2).astype(np.float32)
+    specials = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 65504.0, 65519.99, 65520.0, 65536.0, 1e10, -1e10,
+                         2.0 ** -24, 2.0 ** -25, 2.0 ** -25 * 1.0000001, 2.0 ** -26, 1e-45, 6.1e-5, 6.103515625e-5], np.float32)
+    rand = rng.integers(0, 2 ** 32, 4_000_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    small = (rng.standard_normal(1_000_000) * 10.0 ** rng.integers(-9, 5, 1_000_000)).astype(np.float32)
+    x = np.concatenate([hv, nxt, prv, mid, specials, rand, small])
+    got = oracle.float_to_half(x)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint16), want[~nan].view(np.uint16))
+
+
+def test_half_encode_then_decode_is_identity_on_every_half():
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    f = np.array([oracle.half_bits_to_float(int(h)) for h in bits[::7]], np.float32)
+    back = oracle.float_to_half(f).view(np.uint16)
+    ok = ~np.isnan(f)
+    assert np.array_equal(back[ok], bits[::7][ok])
+
+
+# ------------------------------------------------------------------ Adam
+def test_adam_first_step_moves_by_alpha_against_the_gradient_sign():
+    # t = 1 from zero moments: delta = alpha * g / (|g| + eps / sqrt(1 - beta2))
+    rng = np.random.default_rng(21)
+    g = (rng.standard_normal(1000) * 10.0 ** rng.integers(-3, 3, 1000)).astype(np.float32)
+    p0 = rng.standard_normal(1000).astype(np.float32)
+    p, m, v = p0.copy(), np.zeros(1000, np.float32), np.zeros(1000, np.float32)
+    alpha, b1, b2, eps = 1e-3, 0.9, 0.999, 1e-8
+    oracle.adam(g, p, m, v, alpha, b1, b2, eps, 0.0, 1)
+    a32, b232 = np.float64(np.float32(alpha)), np.float64(np.float32(b2))
+    g64 = g.astype(np.float64)
+    want = p0.astype(np.float64) - a32 * g64 / (np.abs(g64) + np.float64(np.float32(eps)) / np.sqrt(1 - b232))
+    assert np.allclose(p, want, rtol=0, atol=2e-7 * np.maximum(1.0, np.abs(want)).max())
+    big = np.abs(g64) > 1e-2                                                  # |g| >> eps / sqrt(1 - beta2)
+    assert big.sum() > 300 and np.allclose(np.abs(p.astype(np.float64) - p0)[big], a32, rtol=2e-3)   # |step| == alpha
+    assert np.allclose(m, (1 - np.float64(np.float32(b1))) * g64, rtol=1e-6)
+    assert np.allclose(v, (1 - b232) * g64 ** 2, rtol=1e-6)
+
+
+def test_adam_constant_gradient_walks_alpha_per_step():
+    alpha, b1, b2, eps, n = 1e-2, 0.9, 0.999, 1e-8, 30
+    g = np.array([0.5, -3.0, 1e-2, -40.0], np.float32)
+    p = np.array([1.0, 1.0, -1.0, 0.0], np.float32)
+    p0 = p.astype(np.float64)
+    m, v = np.zeros(4, np.float32), np.zeros(4, np.float32)
+    for t in range(1, n + 1):
+        oracle.adam(g, p, m, v, alpha, b1, b2, eps, 0.0, t)
+        assert np.allclose(p, p0 - t * np.float64(np.float32(alpha)) * np.sign(g), rtol=0, atol=t * 2e-6)
+        assert np.allclose(m, g.astype(np.float64) * (1 - np.float64(np.float32(b1)) ** t), rtol=1e-5)
+        assert np.allclose(v, g.astype(np.float64) ** 2 * (1 - np.float64(np.float32(b2)) ** t), rtol=1e-4)
+
+
+def test_adam_is_invariant_to_gradient_scale():
+    rng = np.random.default_rng(22)
+    g = rng.standard_normal(500).astype(np.float32)
+    outs = []
+    for scale in (1.0, 64.0):                      # power of two: every intermediate scales exactly
+        p, m, v = np.ones(500, np.float32), np.zeros(500, np.float32), np.zeros(500, np.float32)
+        for t in range(1, 6):
+            oracle.adam(g * np.float32(scale), p, m, v, 1e-3, 0.9, 0.999, 0.0, 0.0, t)
+        outs.append(p.copy())
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_adam_weight_decay_enters_through_the_gradient():
+    rng = np.random.default_rng(23)
+    p0 = rng.standard_normal(300).astype(np.float32)
+    wd = 0.25
+    a = [p0.copy(), np.zeros(300, np.float32), np.zeros(300, np.float32)]
+    b = [p0.copy(), np.zeros(300, np.float32), np.zeros(300, np.float32)]
+    oracle.adam(np.zeros(300, np.float32), *a, 1e-3, 0.9, 0.999, 1e-8, wd, 1)
+    oracle.adam(np.float32(wd) * p0, *b, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1)   # 0 + wd*p == wd*p exactly
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_adam_against_torch():
+    import torch
+    rng = np.random.default_rng(24)
+    n, alpha, b1, b2, eps = 3000, 1e-3, 0.9, 0.999, 1e-8
+    p0 = rng.standard_normal(n).astype(np.float32)
+    p, m, v = p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    tp = torch.nn.Parameter(torch.tensor(p0.astype(np.float64)))
+    opt = torch.optim.Adam([tp], lr=float(np.float32(alpha)), betas=(float(np.float32(b1)), float(np.float32(b2))),
+                           eps=float(np.float32(eps)))
+    for t in range(1, 8):
+        g = rng.standard_normal(n).astype(np.float32)       # |g| >> eps: the two eps placements coincide
+        oracle.adam(g, p, m, v, alpha, b1, b2, eps, 0.0, t)
+        tp.grad = torch.tensor(g.astype(np.float64))
+        opt.step()
+    tpn = tp.detach().numpy()
+    assert np.max(np.abs(p - tpn)) <= 2e-6 * max(np.abs(tpn).max(), 1.0)
+
+
+def test_adam_lr_closed_form():
+    for t in (1, 2, 10, 1000):
+        want = np.float64(np.float32(1e-3)) * np.sqrt(1 - np.float64(np.float32(0.999)) ** t) / (1 - np.float64(np.float32(0.9)) ** t)
+        assert oracle.adam_lr(1e-3, 0.9, 0.999, t) == np.float32(want)
