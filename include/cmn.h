@@ -28,7 +28,8 @@
  *    kernel entry points only enqueue work and do not synchronise;
  *  - the library never allocates or frees device memory;
  *  - a plan may be used by one host thread at a time;
- *  - gradients are read-only; parameters and velocities are updated in place;
+ *  - gradients are read-only (except under CMN_MEAN_TO_ALL_REPLICAS); parameters,
+ *    velocities and Adam moments are updated in place;
  *    parameters, velocities, mean gradients and all sums are float32;
  *  - no tensor may overlap another, except that mean_grad_ptrs[t] may equal
  *    replica 0's gradient tensor grad_ptrs[t] when grad_dtype is CMN_F32.
@@ -61,20 +62,38 @@ enum cmn_dtype {
     CMN_F16 = 1  /* gradients stored as IEEE binary16, decoded exactly and summed in binary32 */
 };
 
-/* One unit of work of the tensor-space kernels (cmn_momentum_sgd, cmn_allreduce_step):
- * `len` consecutive elements of tensor `tensor` starting at element `e0`, all inside
- * one ring chunk whose sum starts at replica `start_rank`.  head_* is the number of
- * leading elements handled one by one before the first 16-byte aligned vector of every
- * stream the kernel touches, or -1 when the tensor's streams have no common alignment
- * and the whole tile is processed element by element.  Exposed for inspection only. */
+/* Where a fused step puts the averaged gradient. */
+enum cmn_mean_dest {
+    CMN_MEAN_NONE = 0,            /* nowhere: only p and the optimizer state are written      */
+    CMN_MEAN_TO_MEAN_GRADS = 1,   /* into the bound mean_grad_ptrs (float32)                   */
+    CMN_MEAN_TO_ALL_REPLICAS = 2  /* over every replica's own gradient tensors, i.e. the
+                                     "every worker receives the average" half of an allreduce;
+                                     rounded to nearest even when gradients are binary16      */
+};
+
+/* Which streams a kernel variant touches; index into cmn_tile.head. */
+enum cmn_head_index {
+    CMN_HEAD_STEP = 0,       /* K gradients, p, v                      (fused MomentumSGD)     */
+    CMN_HEAD_STEP_MEAN = 1,  /* ... plus mean gradient                                          */
+    CMN_HEAD_SGD = 2,        /* mean gradient, p, v                    (cmn_momentum_sgd)      */
+    CMN_HEAD_ADAM = 3,       /* K gradients, p, m, v                   (fused Adam)            */
+    CMN_HEAD_ADAM_MEAN = 4,  /* ... plus mean gradient                                          */
+    CMN_HEAD_ADAM_OPT = 5    /* mean gradient, p, m, v                 (cmn_adam)              */
+};
+
+/* One unit of work of the tensor-space kernels: `len` consecutive elements of tensor
+ * `tensor` starting at element `e0`, all inside one ring chunk whose sum starts at replica
+ * `start_rank`.  head[i] is the number of leading elements handled one by one before the
+ * first 16-byte aligned vector of every stream variant i touches, or -1 when those streams
+ * have no common alignment (or are not bound) and the whole tile is processed element by
+ * element.  Exposed for inspection only. */
 typedef struct cmn_tile {
     int64_t e0;
     int32_t len;
     int32_t tensor;
     int32_t start_rank;
-    int32_t head_step;      /* cmn_allreduce_step without mean-gradient output */
-    int32_t head_step_mean; /* cmn_allreduce_step with mean-gradient output    */
-    int32_t head_sgd;       /* cmn_momentum_sgd                                 */
+    int32_t reserved;
+    int8_t head[8];
 } cmn_tile;
 
 /* Create a plan for `n_tensors` tensors of numel[t] >= 0 elements (host array, copied),
@@ -99,7 +118,9 @@ size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_
  * pointer arrays (same meaning as in cmn_plan_bind; addresses are only inspected,
  * never dereferenced) into tiles[0 .. cmn_plan_tile_count).  For tests and tooling. */
 int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, void *const *param_ptrs,
-                            void *const *vel_ptrs, void *const *mean_grad_ptrs, cmn_tile *tiles /* host */);
+                            void *const *vel_ptrs, void *const *mean_grad_ptrs,
+                            void *const *second_moment_ptrs /* as cmn_plan_bind_adam, or NULL */,
+                            cmn_tile *tiles /* host */);
 
 /* Bind device tensors to the plan and upload the plan's tables into `dev_workspace`
  * (device, 256-byte aligned, cmn_plan_workspace_bytes long; must outlive all later
@@ -141,11 +162,47 @@ int cmn_momentum_sgd(const cmn_plan *plan, float lr, float mu, float wd, void *s
 
 /* S1..S5 fused into one kernel launch with no intermediate buffer: for every element
  * read the K replicas' gradients in the fixed order, sum, multiply by 1.0f/(float)K,
- * apply the MomentumSGD rule above to p and v in place, and, if write_mean_grad != 0,
- * also store the mean gradient to the bound mean_grad_ptrs.  Results are identical,
- * bit for bit, to cmn_pack -> cmn_ring_reduce -> cmn_scale_unpack -> cmn_momentum_sgd. */
-int cmn_allreduce_step(const cmn_plan *plan, float lr, float mu, float wd, int write_mean_grad,
-                       void *stream);
+ * apply the MomentumSGD rule above to p and v in place, and put the averaged gradient
+ * where mean_dest (a cmn_mean_dest; 0 and 1 keep the meaning of a boolean) says.
+ * With CMN_MEAN_TO_ALL_REPLICAS the bound gradient tensors are overwritten.  Results are
+ * identical, bit for bit, to cmn_pack -> cmn_ring_reduce -> cmn_scale_unpack ->
+ * cmn_momentum_sgd. */
+int cmn_allreduce_step(const cmn_plan *plan, float lr, float mu, float wd, int mean_dest, void *stream);
+
+/* The same step restricted to tensors [tensor_begin, tensor_end) of the list: the unit a
+ * training loop launches per layer group as soon as that group's gradients exist (the
+ * building block for overlapping the exchange with the backward pass, which the paper's
+ * conclusions name as future work).  Ring chunks and fold order are those of the whole list,
+ * so stepping every tensor once, in any grouping and order, equals one cmn_allreduce_step.
+ * Errors: CMN_EINVAL unless 0 <= tensor_begin <= tensor_end <= n_tensors. */
+int cmn_allreduce_step_range(const cmn_plan *plan, int tensor_begin, int tensor_end, float lr, float mu,
+                             float wd, int mean_dest, void *stream);
+
+/* Bind the second-moment tensors of Adam (host array of T device float32 pointers).  The
+ * first moment lives in the tensors bound as vel_ptrs.  Call after cmn_plan_bind (which must
+ * have bound parameters); re-uploads the plan's tables and waits for `stream`. */
+int cmn_plan_bind_adam(cmn_plan *plan, void *const *second_moment_ptrs /* host [T] */, void *stream);
+
+/* Fused step with Adam in place of MomentumSGD (the optimizer the paper's Listing 1 wraps;
+ * Section 3.3: the multi-node optimizer behaves like the optimizer it wraps).  Per element,
+ * with g the averaged gradient and t >= 1 the iteration number:
+ *     g' = g + wd * p                       (skipped when wd == 0)
+ *     m  = m + (1 - beta1) * (g' - m)
+ *     v  = v + (1 - beta2) * (g'*g' - v)
+ *     p  = p - lr_t * m / (sqrt(v) + eps),  lr_t = alpha * sqrt(1 - beta2^t) / (1 - beta1^t)
+ * each operation rounded to float32 once, sqrt and division correctly rounded; lr_t is formed
+ * in double on the host and rounded once.  Errors as cmn_allreduce_step, CMN_EINVAL if t < 1,
+ * CMN_EUNBOUND without cmn_plan_bind_adam. */
+int cmn_allreduce_adam_step(const cmn_plan *plan, float alpha, float beta1, float beta2, float eps, float wd,
+                            int t, int mean_dest, void *stream);
+int cmn_allreduce_adam_step_range(const cmn_plan *plan, int tensor_begin, int tensor_end, float alpha,
+                                  float beta1, float beta2, float eps, float wd, int t, int mean_dest,
+                                  void *stream);
+
+/* Adam on its own, reading the bound mean gradients (the staged counterpart, like
+ * cmn_momentum_sgd). */
+int cmn_adam(const cmn_plan *plan, float alpha, float beta1, float beta2, float eps, float wd, int t,
+             void *stream);
 
 /* Static, never NULL. */
 const char *cmn_strerror(int status);

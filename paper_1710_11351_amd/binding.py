@@ -22,14 +22,18 @@ CMN_F32, CMN_F16 = 0, 1
 _DT = {"f32": CMN_F32, "f16": CMN_F16, CMN_F32: CMN_F32, CMN_F16: CMN_F16}
 
 
+CMN_MEAN_NONE, CMN_MEAN_TO_MEAN_GRADS, CMN_MEAN_TO_ALL_REPLICAS = 0, 1, 2
+(CMN_HEAD_STEP, CMN_HEAD_STEP_MEAN, CMN_HEAD_SGD, CMN_HEAD_ADAM, CMN_HEAD_ADAM_MEAN,
+ CMN_HEAD_ADAM_OPT) = range(6)
+
+
 class cmn_tile(ctypes.Structure):
     _fields_ = [("e0", ctypes.c_int64), ("len", ctypes.c_int32), ("tensor", ctypes.c_int32),
-                ("start_rank", ctypes.c_int32), ("head_step", ctypes.c_int32),
-                ("head_step_mean", ctypes.c_int32), ("head_sgd", ctypes.c_int32)]
+                ("start_rank", ctypes.c_int32), ("reserved", ctypes.c_int32), ("head", ctypes.c_int8 * 8)]
 
 
 TILE_DTYPE = np.dtype([("e0", "<i8"), ("len", "<i4"), ("tensor", "<i4"), ("start_rank", "<i4"),
-                       ("head_step", "<i4"), ("head_step_mean", "<i4"), ("head_sgd", "<i4")])
+                       ("reserved", "<i4"), ("head", "i1", (8,))])
 
 
 class CmnError(RuntimeError):
@@ -62,7 +66,9 @@ def lib() -> ctypes.CDLL:
     L.cmn_plan_workspace_bytes.restype = ctypes.c_size_t
     L.cmn_plan_workspace_bytes.argtypes = [vp]
     L.cmn_plan_describe_tiles.restype = ctypes.c_int
-    L.cmn_plan_describe_tiles.argtypes = [vp, vpp, vpp, vpp, vpp, ctypes.POINTER(cmn_tile)]
+    L.cmn_plan_describe_tiles.argtypes = [vp, vpp, vpp, vpp, vpp, vpp, ctypes.POINTER(cmn_tile)]
+    L.cmn_plan_bind_adam.restype = ctypes.c_int
+    L.cmn_plan_bind_adam.argtypes = [vp, vpp, vp]
     L.cmn_plan_bind.restype = ctypes.c_int
     L.cmn_plan_bind.argtypes = [vp, vp, vpp, vpp, vpp, vpp, vp]
     L.cmn_pack.restype = ctypes.c_int
@@ -75,6 +81,16 @@ def lib() -> ctypes.CDLL:
     L.cmn_momentum_sgd.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, vp]
     L.cmn_allreduce_step.restype = ctypes.c_int
     L.cmn_allreduce_step.argtypes = [vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_int, vp]
+    f = ctypes.c_float
+    L.cmn_allreduce_step_range.restype = ctypes.c_int
+    L.cmn_allreduce_step_range.argtypes = [vp, ctypes.c_int, ctypes.c_int, f, f, f, ctypes.c_int, vp]
+    L.cmn_allreduce_adam_step.restype = ctypes.c_int
+    L.cmn_allreduce_adam_step.argtypes = [vp, f, f, f, f, f, ctypes.c_int, ctypes.c_int, vp]
+    L.cmn_allreduce_adam_step_range.restype = ctypes.c_int
+    L.cmn_allreduce_adam_step_range.argtypes = [vp, ctypes.c_int, ctypes.c_int, f, f, f, f, f, ctypes.c_int,
+                                                ctypes.c_int, vp]
+    L.cmn_adam.restype = ctypes.c_int
+    L.cmn_adam.argtypes = [vp, f, f, f, f, f, ctypes.c_int, vp]
     L.cmn_strerror.restype = ctypes.c_char_p
     L.cmn_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -149,14 +165,18 @@ def cmn_plan_workspace_bytes(h) -> int:
     return lib().cmn_plan_workspace_bytes(h)
 
 
-def cmn_plan_describe_tiles(h, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs):
+def cmn_plan_describe_tiles(h, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, second_moment_ptrs=None):
     """Returns (status, numpy structured array of tiles).  Pointers are ints or tensors."""
     n = max(0, cmn_plan_tile_count(h))
     out = np.zeros(n, dtype=TILE_DTYPE)
     rc = lib().cmn_plan_describe_tiles(h, _ptr_array(grad_ptrs), _ptr_array(param_ptrs), _ptr_array(vel_ptrs),
-                                       _ptr_array(mean_grad_ptrs),
+                                       _ptr_array(mean_grad_ptrs), _ptr_array(second_moment_ptrs),
                                        out.ctypes.data_as(ctypes.POINTER(cmn_tile)) if n else None)
     return rc, out
+
+
+def cmn_plan_bind_adam(h, second_moment_ptrs, stream=None) -> int:
+    return lib().cmn_plan_bind_adam(h, _ptr_array(second_moment_ptrs), _stream(stream))
 
 
 def cmn_plan_bind(h, dev_workspace, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, stream=None) -> int:
@@ -180,8 +200,29 @@ def cmn_momentum_sgd(h, lr: float, mu: float, wd: float, stream=None) -> int:
     return lib().cmn_momentum_sgd(h, lr, mu, wd, _stream(stream))
 
 
-def cmn_allreduce_step(h, lr: float, mu: float, wd: float, write_mean_grad: bool = False, stream=None) -> int:
-    return lib().cmn_allreduce_step(h, lr, mu, wd, int(bool(write_mean_grad)), _stream(stream))
+def cmn_allreduce_step(h, lr: float, mu: float, wd: float, mean_dest: int = CMN_MEAN_NONE, stream=None) -> int:
+    return lib().cmn_allreduce_step(h, lr, mu, wd, int(mean_dest), _stream(stream))
+
+
+def cmn_allreduce_step_range(h, tensor_begin: int, tensor_end: int, lr: float, mu: float, wd: float,
+                             mean_dest: int = CMN_MEAN_NONE, stream=None) -> int:
+    return lib().cmn_allreduce_step_range(h, int(tensor_begin), int(tensor_end), lr, mu, wd, int(mean_dest),
+                                          _stream(stream))
+
+
+def cmn_allreduce_adam_step(h, alpha, beta1, beta2, eps, wd, t: int, mean_dest: int = CMN_MEAN_NONE,
+                            stream=None) -> int:
+    return lib().cmn_allreduce_adam_step(h, alpha, beta1, beta2, eps, wd, int(t), int(mean_dest), _stream(stream))
+
+
+def cmn_allreduce_adam_step_range(h, tensor_begin: int, tensor_end: int, alpha, beta1, beta2, eps, wd, t: int,
+                                  mean_dest: int = CMN_MEAN_NONE, stream=None) -> int:
+    return lib().cmn_allreduce_adam_step_range(h, int(tensor_begin), int(tensor_end), alpha, beta1, beta2, eps, wd,
+                                               int(t), int(mean_dest), _stream(stream))
+
+
+def cmn_adam(h, alpha, beta1, beta2, eps, wd, t: int, stream=None) -> int:
+    return lib().cmn_adam(h, alpha, beta1, beta2, eps, wd, int(t), _stream(stream))
 
 
 # ------------------------------------------------------------------ convenience wrapper
@@ -240,8 +281,29 @@ class Plan:
     def momentum_sgd(self, lr, mu, wd, stream=None) -> None:
         _check(cmn_momentum_sgd(self.h, lr, mu, wd, stream), "cmn_momentum_sgd")
 
-    def allreduce_step(self, lr, mu, wd, write_mean_grad=False, stream=None) -> None:
-        _check(cmn_allreduce_step(self.h, lr, mu, wd, write_mean_grad, stream), "cmn_allreduce_step")
+    def allreduce_step(self, lr, mu, wd, write_mean_grad=False, stream=None, mean_dest=None) -> None:
+        dest = int(bool(write_mean_grad)) if mean_dest is None else int(mean_dest)
+        _check(cmn_allreduce_step(self.h, lr, mu, wd, dest, stream), "cmn_allreduce_step")
+
+    def allreduce_step_range(self, tensor_begin, tensor_end, lr, mu, wd, mean_dest=CMN_MEAN_NONE, stream=None) -> None:
+        _check(cmn_allreduce_step_range(self.h, tensor_begin, tensor_end, lr, mu, wd, mean_dest, stream),
+               "cmn_allreduce_step_range")
+
+    def bind_adam(self, second_moments, stream=None) -> None:
+        _check(cmn_plan_bind_adam(self.h, second_moments, stream), "cmn_plan_bind_adam")
+        self._keep = (self._keep, second_moments)
+
+    def allreduce_adam_step(self, alpha, beta1, beta2, eps, wd, t, mean_dest=CMN_MEAN_NONE, stream=None) -> None:
+        _check(cmn_allreduce_adam_step(self.h, alpha, beta1, beta2, eps, wd, t, mean_dest, stream),
+               "cmn_allreduce_adam_step")
+
+    def allreduce_adam_step_range(self, tensor_begin, tensor_end, alpha, beta1, beta2, eps, wd, t,
+                                  mean_dest=CMN_MEAN_NONE, stream=None) -> None:
+        _check(cmn_allreduce_adam_step_range(self.h, tensor_begin, tensor_end, alpha, beta1, beta2, eps, wd, t,
+                                             mean_dest, stream), "cmn_allreduce_adam_step_range")
+
+    def adam(self, alpha, beta1, beta2, eps, wd, t, stream=None) -> None:
+        _check(cmn_adam(self.h, alpha, beta1, beta2, eps, wd, t, stream), "cmn_adam")
 
 
 # ------------------------------------------------------------------ device-memory plumbing for callers

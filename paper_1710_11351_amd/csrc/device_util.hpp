@@ -29,6 +29,8 @@ template <> struct GradT<CMN_F32> {
         acc[0] = acc[0] + r.x; acc[1] = acc[1] + r.y; acc[2] = acc[2] + r.z; acc[3] = acc[3] + r.w;
     }
     static __device__ __forceinline__ float decode(elem x) { return x; }
+    static __device__ __forceinline__ elem encode(float x) { return x; }
+    static __device__ __forceinline__ raw encode_vec(const float (&g)[4]) { return raw{g[0], g[1], g[2], g[3]}; }
 };
 
 template <> struct GradT<CMN_F16> {
@@ -40,6 +42,13 @@ template <> struct GradT<CMN_F16> {
         for (int i = 0; i < 8; ++i) acc[i] = acc[i] + static_cast<float>(r[i]);  // exact widening
     }
     static __device__ __forceinline__ float decode(elem x) { return static_cast<float>(x); }
+    static __device__ __forceinline__ elem encode(float x) { return static_cast<elem>(x); }  // nearest even
+    static __device__ __forceinline__ raw encode_vec(const float (&g)[8]) {
+        raw r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = static_cast<elem>(g[i]);
+        return r;
+    }
 };
 
 template <typename V>
@@ -70,6 +79,10 @@ __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
 }
 
+__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f16x8 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
+}
+
 // The K-term sum starts from -0.0f because x + (-0.0f) == x for every x, signed
 // zeros included, so the first addition reproduces the first gradient exactly.
 __device__ __forceinline__ constexpr float sum_identity() { return -0.0f; }
@@ -80,17 +93,43 @@ __device__ __forceinline__ int ring_rank(int s, int j, int K) {
     return r >= K ? r - K : r;
 }
 
-// MomentumSGD on one element; gbar is the averaged gradient.
-__device__ __forceinline__ void sgd_update(float gbar, float &p, float &v, float lr, float mu, float wd) {
+// Optimizer hyper-parameters as the kernels receive them (by value).
+//   MomentumSGD: a = lr, b = mu.        Adam: a = lr_t, b = 1 - beta1, c = 1 - beta2, d = eps.
+struct OptArgs {
+    float a, b, c, d, wd;
+};
+
+enum { OPT_SGD = 0, OPT_ADAM = 1 };
+
+// One element of the optimizer step; gbar is the averaged gradient, s1 the velocity
+// (MomentumSGD) or first moment (Adam), s2 Adam's second moment.  Every operation
+// rounds to float32 once; sqrt and the division are the correctly rounded ones.
+template <int OPT>
+__device__ __forceinline__ void opt_update(float gbar, float &p, float &s1, float &s2, const OptArgs &o) {
     float g = gbar;
-    if (wd != 0.0f) {
-        const float d = wd * p;
-        g = g + d;
+    if (o.wd != 0.0f) {
+        const float dec = o.wd * p;
+        g = g + dec;
     }
-    const float t1 = mu * v;
-    const float t2 = lr * g;
-    v = t1 - t2;
-    p = p + v;
+    if (OPT == OPT_SGD) {
+        const float t1 = o.b * s1;
+        const float t2 = o.a * g;
+        s1 = t1 - t2;
+        p = p + s1;
+    } else {
+        const float t1 = g - s1;
+        const float t2 = o.b * t1;
+        s1 = s1 + t2;
+        const float t3 = g * g;
+        const float t4 = t3 - s2;
+        const float t5 = o.c * t4;
+        s2 = s2 + t5;
+        const float root = sqrtf(s2);
+        const float den = root + o.d;
+        const float q = s1 / den;
+        const float u = o.a * q;
+        p = p - u;
+    }
 }
 
 }  // namespace cmn

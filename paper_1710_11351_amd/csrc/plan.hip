@@ -22,6 +22,7 @@ static WorkspaceLayout make_layout(int T, int K, int64_t n_tiles) {
     w.param_ptrs = o; o = round256(o + sizeof(void *) * size_t(T));
     w.vel_ptrs = o;   o = round256(o + sizeof(void *) * size_t(T));
     w.mean_ptrs = o;  o = round256(o + sizeof(void *) * size_t(T));
+    w.state2_ptrs = o; o = round256(o + sizeof(void *) * size_t(T));
     w.tiles = o;      o = round256(o + sizeof(cmn_tile) * size_t(n_tiles));
     w.total = o < 256 ? 256 : o;
     return w;
@@ -71,35 +72,50 @@ static int common_head(const void *const *g, int n_g, int g_elem_bytes, int vec,
 }
 
 void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *param_ptrs,
-                 void *const *vel_ptrs, void *const *mean_ptrs, cmn_tile *out) {
+                 void *const *vel_ptrs, void *const *mean_ptrs, void *const *state2_ptrs, cmn_tile *out) {
     const int vec = vec_elems(p.dtype), geb = elem_bytes(p.dtype);
-    std::vector<int> h_step(p.T, -1), h_step_mean(p.T, -1), h_sgd(p.T, -1);
+    std::vector<int8_t> h(size_t(p.T) * 8, int8_t(-1));   // per tensor: head of element 0 per variant
     std::vector<const void *> g(p.K);
+    const bool opt = param_ptrs && vel_ptrs;
     for (int t = 0; t < p.T; ++t) {
         if (p.numel[t] == 0) continue;
-        const void *f32[3];
-        if (grad_ptrs && param_ptrs && vel_ptrs) {
+        int8_t *ht = &h[size_t(t) * 8];
+        const void *f32[5];
+        if (grad_ptrs && opt) {
             for (int k = 0; k < p.K; ++k) g[k] = grad_ptrs[size_t(k) * p.T + t];
             f32[0] = param_ptrs[t]; f32[1] = vel_ptrs[t];
-            h_step[t] = common_head(g.data(), p.K, geb, vec, f32, 2);
+            ht[CMN_HEAD_STEP] = int8_t(common_head(g.data(), p.K, geb, vec, f32, 2));
             if (mean_ptrs) {
                 f32[2] = mean_ptrs[t];
-                h_step_mean[t] = common_head(g.data(), p.K, geb, vec, f32, 3);
+                ht[CMN_HEAD_STEP_MEAN] = int8_t(common_head(g.data(), p.K, geb, vec, f32, 3));
+            }
+            if (state2_ptrs) {
+                f32[2] = state2_ptrs[t];
+                ht[CMN_HEAD_ADAM] = int8_t(common_head(g.data(), p.K, geb, vec, f32, 3));
+                if (mean_ptrs) {
+                    f32[3] = mean_ptrs[t];
+                    ht[CMN_HEAD_ADAM_MEAN] = int8_t(common_head(g.data(), p.K, geb, vec, f32, 4));
+                }
             }
         }
-        if (mean_ptrs && param_ptrs && vel_ptrs) {
+        if (mean_ptrs && opt) {
             f32[0] = mean_ptrs[t]; f32[1] = param_ptrs[t]; f32[2] = vel_ptrs[t];
-            h_sgd[t] = common_head(nullptr, 0, 4, 4, f32, 3);
+            ht[CMN_HEAD_SGD] = int8_t(common_head(nullptr, 0, 4, 4, f32, 3));
+            if (state2_ptrs) {
+                f32[3] = state2_ptrs[t];
+                ht[CMN_HEAD_ADAM_OPT] = int8_t(common_head(nullptr, 0, 4, 4, f32, 4));
+            }
         }
     }
     int64_t i = 0;
     for_each_tile(p, [&](int t, int64_t e0, int32_t len, int32_t start) {
         cmn_tile &tl = out[i++];
-        tl.e0 = e0; tl.len = len; tl.tensor = t; tl.start_rank = start;
-        auto head = [&](int a, int v) { return a < 0 ? -1 : int32_t(((a - e0) % v + v) % v); };
-        tl.head_step = head(h_step[t], vec);
-        tl.head_step_mean = head(h_step_mean[t], vec);
-        tl.head_sgd = head(h_sgd[t], 4);
+        tl.e0 = e0; tl.len = len; tl.tensor = t; tl.start_rank = start; tl.reserved = 0;
+        for (int v = 0; v < 8; ++v) {
+            const int a = h[size_t(t) * 8 + v];
+            const int w = (v == CMN_HEAD_SGD || v == CMN_HEAD_ADAM_OPT) ? 4 : vec;
+            tl.head[v] = a < 0 ? int8_t(-1) : int8_t(((a - e0) % w + w) % w);
+        }
     });
 }
 
@@ -154,7 +170,14 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
         if (v >= 1 && v <= 64) iters = v;
     }
     p->tile_elems = kBlock * vec_elems(grad_dtype) * iters;
-    p->n_tiles = for_each_tile(*p, [](int, int64_t, int32_t, int32_t) {});
+    try {
+        p->first_tile.assign(size_t(n_tensors) + 1, 0);
+    } catch (...) { delete p; return CMN_ENOMEM; }
+    {
+        std::vector<int64_t> &ft = p->first_tile;
+        p->n_tiles = for_each_tile(*p, [&ft](int t, int64_t, int32_t, int32_t) { ++ft[size_t(t) + 1]; });
+        for (int t = 0; t < n_tensors; ++t) ft[size_t(t) + 1] += ft[size_t(t)];
+    }
     if (p->n_tiles > (int64_t(1) << 31) - 1) { delete p; return CMN_ESIZE; }
     p->ws = make_layout(p->T, p->K, p->n_tiles);
     *out = p;
@@ -184,16 +207,38 @@ static int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows,
 }
 
 int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, void *const *param_ptrs,
-                            void *const *vel_ptrs, void *const *mean_grad_ptrs, cmn_tile *tiles) {
+                            void *const *vel_ptrs, void *const *mean_grad_ptrs, void *const *second_moment_ptrs,
+                            cmn_tile *tiles) {
     if (!plan || (!tiles && plan->n_tiles > 0)) return CMN_ENULL;
     int rc;
     if (grad_ptrs && (rc = check_ptr_array(plan, grad_ptrs, plan->K, elem_bytes(plan->dtype)))) return rc;
     if (param_ptrs && (rc = check_ptr_array(plan, param_ptrs, 1, 4))) return rc;
     if (vel_ptrs && (rc = check_ptr_array(plan, vel_ptrs, 1, 4))) return rc;
     if (mean_grad_ptrs && (rc = check_ptr_array(plan, mean_grad_ptrs, 1, 4))) return rc;
+    if (second_moment_ptrs && (rc = check_ptr_array(plan, second_moment_ptrs, 1, 4))) return rc;
     try {
-        build_tiles(*plan, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, tiles);
+        build_tiles(*plan, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, second_moment_ptrs, tiles);
     } catch (...) { return CMN_ENOMEM; }
+    return CMN_OK;
+}
+
+// Rebuild the tile table inside the staging image from the pointer tables it holds and
+// copy the image to the device workspace.
+static int upload_image(cmn_plan *p, void *dev_workspace, hipStream_t s) {
+    unsigned char *img = p->staging.data();
+    auto tab = [&](size_t off) { return reinterpret_cast<void *const *>(img + off); };
+    try {
+        std::vector<const void *> flat;
+        if (p->have_grads) {
+            flat.assign(reinterpret_cast<const void *const *>(img + p->ws.grad_rows),
+                        reinterpret_cast<const void *const *>(img + p->ws.grad_rows) + size_t(p->K) * p->T);
+        }
+        build_tiles(*p, p->have_grads ? flat.data() : nullptr, p->have_opt ? tab(p->ws.param_ptrs) : nullptr,
+                    p->have_opt ? tab(p->ws.vel_ptrs) : nullptr, p->have_mean ? tab(p->ws.mean_ptrs) : nullptr,
+                    p->have_state2 ? tab(p->ws.state2_ptrs) : nullptr, reinterpret_cast<cmn_tile *>(img + p->ws.tiles));
+    } catch (...) { return CMN_ENOMEM; }
+    if (hipMemcpyAsync(dev_workspace, img, p->ws.total, hipMemcpyHostToDevice, s) != hipSuccess) return CMN_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return CMN_EHIP;
     return CMN_OK;
 }
 
@@ -228,19 +273,25 @@ int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_p
     if (param_ptrs) std::memcpy(img + p->ws.param_ptrs, param_ptrs, sizeof(void *) * T);
     if (vel_ptrs) std::memcpy(img + p->ws.vel_ptrs, vel_ptrs, sizeof(void *) * T);
     if (mean_grad_ptrs) std::memcpy(img + p->ws.mean_ptrs, mean_grad_ptrs, sizeof(void *) * T);
-    try {
-        build_tiles(*p, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs,
-                    reinterpret_cast<cmn_tile *>(img + p->ws.tiles));
-    } catch (...) { return CMN_ENOMEM; }
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(dev_workspace, img, p->ws.total, hipMemcpyHostToDevice, s) != hipSuccess) return CMN_EHIP;
-    if (hipStreamSynchronize(s) != hipSuccess) return CMN_EHIP;
-    p->dev_ws = static_cast<char *>(dev_workspace);
     p->have_grads = grad_ptrs != nullptr;
     p->have_opt = param_ptrs != nullptr;
     p->have_mean = mean_grad_ptrs != nullptr;
+    p->have_state2 = false;
+    if (int rc2 = upload_image(p, dev_workspace, static_cast<hipStream_t>(stream))) return rc2;
+    p->dev_ws = static_cast<char *>(dev_workspace);
     p->bound = true;
+    return CMN_OK;
+}
+
+int cmn_plan_bind_adam(cmn_plan *plan, void *const *second_moment_ptrs, void *stream) {
+    if (!plan || !second_moment_ptrs) return CMN_ENULL;
+    if (!plan->bound || !plan->have_opt) return CMN_EUNBOUND;
+    if (int rc = check_ptr_array(plan, second_moment_ptrs, 1, 4)) return rc;
+    std::memcpy(plan->staging.data() + plan->ws.state2_ptrs, second_moment_ptrs, sizeof(void *) * size_t(plan->T));
+    plan->have_state2 = true;
+    plan->bound = false;
+    if (int rc = upload_image(plan, plan->dev_ws, static_cast<hipStream_t>(stream))) return rc;
+    plan->bound = true;
     return CMN_OK;
 }
 

@@ -28,6 +28,7 @@ struct WorkspaceLayout {
     size_t param_ptrs = 0;   // float* [T]
     size_t vel_ptrs = 0;     // float* [T]
     size_t mean_ptrs = 0;    // float* [T]
+    size_t state2_ptrs = 0;  // float* [T]   Adam second moments
     size_t tiles = 0;        // cmn_tile [n_tiles]
     size_t total = 0;
 };
@@ -40,10 +41,11 @@ struct cmn_plan {
     std::vector<int64_t> numel;  // [T]
     std::vector<int64_t> off;    // [T+1]
     int64_t N = 0, chunk_elems = 0, L = 0, n_tiles = 0;
+    std::vector<int64_t> first_tile;  // [T+1] index of each tensor's first tile in the table
     cmn::WorkspaceLayout ws;
 
     // state set by cmn_plan_bind
-    bool bound = false, have_grads = false, have_opt = false, have_mean = false;
+    bool bound = false, have_grads = false, have_opt = false, have_mean = false, have_state2 = false;
     char *dev_ws = nullptr;
     std::vector<unsigned char> staging;  // host image of the workspace
 };
@@ -52,7 +54,7 @@ namespace cmn {
 
 // Fills out[0..n_tiles) for the given pointer arrays (may be null: heads become -1).
 void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *param_ptrs,
-                 void *const *vel_ptrs, void *const *mean_ptrs, cmn_tile *out);
+                 void *const *vel_ptrs, void *const *mean_ptrs, void *const *state2_ptrs, cmn_tile *out);
 
 // Shared argument checks of the kernel entry points.
 int check_launch(const cmn_plan *p);

@@ -1,0 +1,196 @@
+// The tensor-space kernel behind cmn_allreduce_step, cmn_allreduce_adam_step, their
+// _range forms, cmn_momentum_sgd and cmn_adam.  A tile names a run of elements of one
+// tensor inside one ring chunk; every thread owns one 16-byte gradient vector of it.
+//   SRC_FOLD: read the K replicas' vectors in the chunk's fold order, sum, scale by 1/K
+//   SRC_MEAN: read the averaged gradient from the bound mean-gradient tensor
+// then apply the optimizer to p and its state in place.  No packed buffer exists.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "device_util.hpp"
+#include "plan.hpp"
+
+#pragma clang fp contract(off)
+
+namespace cmn {
+
+enum { SRC_FOLD = 0, SRC_MEAN = 1 };
+
+template <int SRC, int MEAN, int OPT>
+__device__ __forceinline__ constexpr int head_index() {
+    return SRC == SRC_MEAN ? (OPT == OPT_ADAM ? CMN_HEAD_ADAM_OPT : CMN_HEAD_SGD)
+           : OPT == OPT_ADAM ? (MEAN == CMN_MEAN_TO_MEAN_GRADS ? CMN_HEAD_ADAM_MEAN : CMN_HEAD_ADAM)
+                             : (MEAN == CMN_MEAN_TO_MEAN_GRADS ? CMN_HEAD_STEP_MEAN : CMN_HEAD_STEP);
+}
+
+// U = gradient vectors requested back to back before the first one is consumed.
+template <int DT, int U, int SRC, int MEAN, int OPT>
+__global__ __launch_bounds__(kBlock) void k_step(
+    const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
+    float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
+    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs, int K, float inv_k, OptArgs o) {
+    using G = GradT<DT>;
+    using elem = typename G::elem;
+    using raw = typename G::raw;
+    constexpr int VEC = SRC == SRC_MEAN ? 4 : G::VEC;
+    constexpr bool ADAM = OPT == OPT_ADAM;
+    constexpr bool USE_MEAN_TENSOR = SRC == SRC_MEAN || MEAN == CMN_MEAN_TO_MEAN_GRADS;
+
+    const cmn_tile tl = tiles[blockIdx.x];
+    const int t = tl.tensor, s = tl.start_rank, len = tl.len;
+    const void *const *gcol = grad_cols + size_t(t) * size_t(K);
+    float *p = param_ptrs[t] + tl.e0;
+    float *s1 = s1_ptrs[t] + tl.e0;
+    float *s2 = ADAM ? s2_ptrs[t] + tl.e0 : nullptr;
+    float *m = USE_MEAN_TENSOR ? mean_ptrs[t] + tl.e0 : nullptr;
+
+    int head = tl.head[head_index<SRC, MEAN, OPT>()];
+    if (head < 0 || head > len) head = len;
+    const int nvec = (len - head) / VEC;
+    const int tail0 = head + nvec * VEC;
+    const unsigned bytes = unsigned(len) * 4u;
+    const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, bytes);
+    const __amdgpu_buffer_rsrc_t s1_out = make_rsrc(s1, bytes);
+    const __amdgpu_buffer_rsrc_t s2_out = make_rsrc(s2, ADAM ? bytes : 0u);
+    const __amdgpu_buffer_rsrc_t m_out = make_rsrc(m, MEAN == CMN_MEAN_TO_MEAN_GRADS ? bytes : 0u);
+
+    for (int vi = threadIdx.x; vi < nvec; vi += kBlock) {
+        const unsigned e = unsigned(head + vi * VEC);
+        f32x4 pv[VEC / 4], s1v[VEC / 4], s2v[VEC / 4];
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            pv[q] = load_vec<f32x4>(p + e + 4 * q);
+            s1v[q] = load_vec<f32x4>(s1 + e + 4 * q);
+            if (ADAM) s2v[q] = load_vec<f32x4>(s2 + e + 4 * q);
+        }
+        float gb[VEC];
+        if (SRC == SRC_MEAN) {
+            const f32x4 g = load_vec<f32x4>(m + e);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) gb[i] = g[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
+            int j = 0;
+            for (; j + U <= K; j += U) {
+                raw g[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    g[u] = load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j + u, K)]) + tl.e0 + e);
+#pragma unroll
+                for (int u = 0; u < U; ++u) G::accumulate(gb, g[u]);
+            }
+            for (; j < K; ++j)
+                G::accumulate(gb, load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e));
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
+        }
+
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float pi = pv[q][i], a = s1v[q][i], b = ADAM ? s2v[q][i] : 0.0f;
+                opt_update<OPT>(gb[4 * q + i], pi, a, b, o);
+                pv[q][i] = pi; s1v[q][i] = a;
+                if (ADAM) s2v[q][i] = b;
+            }
+            if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS)
+                store_through(m_out, (e + 4 * q) * 4u, f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]});
+            if (ADAM) store_through(s2_out, (e + 4 * q) * 4u, s2v[q]);
+            store_through(s1_out, (e + 4 * q) * 4u, s1v[q]);
+            store_through(p_out, (e + 4 * q) * 4u, pv[q]);
+        }
+        if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
+            // every gradient of this vector has been read above; hand the average to each replica
+            const raw avg = G::encode_vec(gb);
+            for (int k = 0; k < K; ++k) {
+                elem *dst = static_cast<elem *>(const_cast<void *>(gcol[k])) + tl.e0;
+                store_through(make_rsrc(dst, unsigned(len) * unsigned(sizeof(elem))), e * unsigned(sizeof(elem)), avg);
+            }
+        }
+    }
+
+    // ragged head and tail of the tile (or the whole tile when its streams share no alignment)
+    const int n_single = head + (len - tail0);
+    for (int i = threadIdx.x; i < n_single; i += kBlock) {
+        const int e = i < head ? i : tail0 + (i - head);
+        float gb;
+        if (SRC == SRC_MEAN) {
+            gb = m[e];
+        } else {
+            float acc = sum_identity();
+            for (int j = 0; j < K; ++j)
+                acc = acc + G::decode(static_cast<const elem *>(gcol[ring_rank(s, j, K)])[tl.e0 + e]);
+            gb = acc * inv_k;
+        }
+        float pi = p[e], a = s1[e], b = ADAM ? s2[e] : 0.0f;
+        opt_update<OPT>(gb, pi, a, b, o);
+        if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS) m[e] = gb;
+        if (ADAM) s2[e] = b;
+        s1[e] = a;
+        p[e] = pi;
+        if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
+            const elem avg = G::encode(gb);
+            for (int k = 0; k < K; ++k) static_cast<elem *>(const_cast<void *>(gcol[k]))[tl.e0 + e] = avg;
+        }
+    }
+}
+
+template <int DT, int SRC, int MEAN, int OPT>
+inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o, hipStream_t s) {
+    constexpr int U = 16;
+    hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
+                       ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
+                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<float *const>(p, p->ws.param_ptrs),
+                       ws_ptr<float *const>(p, p->ws.vel_ptrs), ws_ptr<float *const>(p, p->ws.state2_ptrs),
+                       ws_ptr<float *const>(p, p->ws.mean_ptrs), p->K, 1.0f / float(p->K), o);
+}
+
+// Fused step (SRC_FOLD) over tensors [t0, t1): validation shared by the SGD and Adam entry points.
+template <int OPT>
+inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, const OptArgs &o, void *stream) {
+    if (int rc = check_launch(plan)) return rc;
+    if (t0 < 0 || t1 < t0 || t1 > plan->T) return CMN_EINVAL;
+    if (mean_dest != CMN_MEAN_NONE && mean_dest != CMN_MEAN_TO_MEAN_GRADS && mean_dest != CMN_MEAN_TO_ALL_REPLICAS)
+        return CMN_EINVAL;
+    if (!plan->have_grads || !plan->have_opt || (mean_dest == CMN_MEAN_TO_MEAN_GRADS && !plan->have_mean))
+        return CMN_EUNBOUND;
+    if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
+    const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
+    if (n == 0) return CMN_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CMN_STEP_CASE(DT, MEAN) launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s)
+    if (plan->dtype == CMN_F32) {
+        if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(CMN_F32, CMN_MEAN_NONE);
+        else if (mean_dest == CMN_MEAN_TO_MEAN_GRADS) CMN_STEP_CASE(CMN_F32, CMN_MEAN_TO_MEAN_GRADS);
+        else CMN_STEP_CASE(CMN_F32, CMN_MEAN_TO_ALL_REPLICAS);
+    } else {
+        if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(CMN_F16, CMN_MEAN_NONE);
+        else if (mean_dest == CMN_MEAN_TO_MEAN_GRADS) CMN_STEP_CASE(CMN_F16, CMN_MEAN_TO_MEAN_GRADS);
+        else CMN_STEP_CASE(CMN_F16, CMN_MEAN_TO_ALL_REPLICAS);
+    }
+#undef CMN_STEP_CASE
+    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+}
+
+// Optimizer alone (SRC_MEAN) over all tensors.
+template <int OPT>
+inline int launch_optimizer(const cmn_plan *plan, const OptArgs &o, void *stream) {
+    if (int rc = check_launch(plan)) return rc;
+    if (!plan->have_opt || !plan->have_mean) return CMN_EUNBOUND;
+    if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
+    if (plan->n_tiles == 0) return CMN_OK;
+    launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
+    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+}
+
+// lr_t of Adam: the bias corrections of both moments folded into the step size.
+inline float adam_step_size(float alpha, float beta1, float beta2, int t) {
+    const double c1 = 1.0 - std::pow(double(beta1), double(t));
+    const double c2 = 1.0 - std::pow(double(beta2), double(t));
+    return float(double(alpha) * std::sqrt(c2) / c1);
+}
+
+}  // namespace cmn

@@ -38,7 +38,7 @@ def assert_update_close(got, want, what, rel=1e-6):
 class DeviceCase:
     """Device tensors of one workload, each tensor its own allocation."""
 
-    def __init__(self, c: wl.Config, ring_rotate=1, misalign=0, with_mean=True):
+    def __init__(self, c: wl.Config, ring_rotate=1, misalign=0, with_mean=True, adam=False):
         import torch
         self.c, self.torch = c, torch
         self.np_g = np.float16 if c.grad_dtype == "f16" else np.float32
@@ -56,6 +56,10 @@ class DeviceCase:
         self.p, self.v = alloc(torch.float32), alloc(torch.float32)
         self.m = alloc(torch.float32) if with_mean else None
         self.plan.bind(self.grads, self.p, self.v, self.m)
+        self.s = None
+        if adam:
+            self.s = alloc(torch.float32)
+            self.plan.bind_adam(self.s)
 
     def set_state(self, p_host, v_host):
         for d, h in zip(self.p, p_host):
@@ -81,16 +85,24 @@ def gen_all_grads(c: wl.Config, step: int, unquantised=False):
         return list(ex.map(lambda k: fn(c, step, k), range(c.K)))
 
 
-def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fused=True, check_packed=True):
-    """Oracle vs HIP on `steps` consecutive iterations with fresh gradients each."""
+ADAM = dict(alpha=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)     # the optimizer's published defaults
+
+
+def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fused=True, check_packed=True,
+               opt="sgd", bucketed=False):
+    """Oracle vs HIP on `steps` consecutive iterations with fresh gradients each.
+    opt: "sgd" (MomentumSGD) or "adam"; bucketed: run the fused step as per-layer-group
+    range calls, last group first, instead of one call."""
     import torch
+    adam = opt == "adam"
     p_o = [x.copy() for x in wl.gen_params(c)]
     v_o = [x.copy() for x in wl.gen_velocity(c)]
+    s_o = [x.copy() for x in wl.gen_velocity(c)]            # Adam's second moments start at zero too
     cases = {}
     if fused:
-        cases["fused"] = DeviceCase(c, ring_rotate, misalign)
+        cases["fused"] = DeviceCase(c, ring_rotate, misalign, adam=adam)
     if staged:
-        cases["staged"] = DeviceCase(c, ring_rotate, misalign)
+        cases["staged"] = DeviceCase(c, ring_rotate, misalign, adam=adam)
     for dc in cases.values():
         dc.set_state(p_o, v_o)
     geo = oracle.Geometry(c.numel, c.n_chunks, c.align_bytes, c.grad_dtype)
@@ -112,7 +124,11 @@ def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fu
         total_o = oracle.direct_fold(geo, packed_o, ring_rotate)
         mean_o = oracle.unpack(geo, oracle.scale(total_o, c.K))
         for t in range(geo.T):
-            oracle.momentum_sgd(mean_o[t], p_o[t], v_o[t], c.lr, c.mu, c.wd)
+            if adam:
+                oracle.adam(mean_o[t], p_o[t], v_o[t], s_o[t], ADAM["alpha"], ADAM["beta1"], ADAM["beta2"],
+                            ADAM["eps"], c.wd, step + 1)
+            else:
+                oracle.momentum_sgd(mean_o[t], p_o[t], v_o[t], c.lr, c.mu, c.wd)
 
         if staged:
             dc = cases["staged"]
@@ -128,16 +144,28 @@ def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fu
             dc.plan.scale_unpack(reduced)
             for t, (a, b) in enumerate(zip(dc.get(dc.m), mean_o)):
                 assert_bit_equal(a, b, f"step {step} staged mean_grad[{t}]")
-            dc.plan.momentum_sgd(c.lr, c.mu, c.wd)
-            _compare_state(dc, p_o, v_o, f"step {step} staged")
+            if adam:
+                dc.plan.adam(ADAM["alpha"], ADAM["beta1"], ADAM["beta2"], ADAM["eps"], c.wd, step + 1)
+            else:
+                dc.plan.momentum_sgd(c.lr, c.mu, c.wd)
+            _compare_state(dc, p_o, v_o, f"step {step} staged", s_o if adam else None)
         if fused:
             dc = cases["fused"]
             write_mean = step % 2 == 0
             if write_mean:
                 for m in dc.m:
                     m.fill_(-5.0)
-            dc.plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=write_mean)
-            _compare_state(dc, p_o, v_o, f"step {step} fused")
+            groups = [(0, geo.T)]
+            if bucketed:                                    # uneven layer groups, output layer first
+                cuts = sorted({0, geo.T, geo.T // 7, geo.T // 3, geo.T // 2, geo.T - 1} & set(range(geo.T + 1)))
+                groups = list(zip(cuts[:-1], cuts[1:]))[::-1] + [(geo.T, geo.T)]
+            for t0, t1 in groups:
+                if adam:
+                    dc.plan.allreduce_adam_step_range(t0, t1, ADAM["alpha"], ADAM["beta1"], ADAM["beta2"], ADAM["eps"],
+                                                      c.wd, step + 1, mean_dest=int(write_mean))
+                else:
+                    dc.plan.allreduce_step_range(t0, t1, c.lr, c.mu, c.wd, mean_dest=int(write_mean))
+            _compare_state(dc, p_o, v_o, f"step {step} fused", s_o if adam else None)
             if write_mean:
                 for t, (a, b) in enumerate(zip(dc.get(dc.m), mean_o)):
                     assert_bit_equal(a, b, f"step {step} fused mean_grad[{t}]")
@@ -145,7 +173,11 @@ def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fu
     return p_o, v_o
 
 
-def _compare_state(dc, p_o, v_o, what):
+def _compare_state(dc, p_o, v_o, what, s_o=None):
+    if s_o is not None:
+        for t, (a, b) in enumerate(zip(dc.get(dc.s), s_o)):
+            assert_update_close(a, b, f"{what} second moment[{t}]")
+            assert_bit_equal(a, b, f"{what} second moment[{t}]")
     for t, (a, b) in enumerate(zip(dc.get(dc.p), p_o)):
         assert_update_close(a, b, f"{what} p[{t}]")     # the stated bar
         assert_bit_equal(a, b, f"{what} p[{t}]")        # what the kernels actually achieve

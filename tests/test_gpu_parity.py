@@ -86,6 +86,61 @@ def test_config2_resnet50_k4_full_size():
     run_parity(wl.config(2), steps=3)
 
 
+# ---- widened rows: bucketed (per layer group) steps, Adam, average handed back to every replica ----
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("opt", ["sgd", "adam"])
+def test_bucketed_range_steps_equal_one_full_step(dtype, opt):
+    numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3, 800, 4096]
+    c = wl.custom_config(numel, K=5, n_chunks=5, grad_dtype=dtype, cfg=98, wd=1e-3)
+    run_parity(c, steps=2, staged=False, opt=opt, bucketed=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("misalign", [0, 3])
+def test_adam_fused_and_staged(dtype, misalign):
+    numel = [1000, 4096, 37, 8192 + 5, 0, 64]
+    c = wl.custom_config(numel, K=6, n_chunks=3, grad_dtype=dtype, cfg=99, wd=5e-4 if misalign else 0.0)
+    run_parity(c, steps=3, opt="adam", misalign=misalign)
+
+
+def test_range_arguments_are_validated():
+    from paper_1710_11351_amd import binding as B
+    from parity_util import DeviceCase
+    dc = DeviceCase(wl.custom_config([100, 200, 300], K=2, n_chunks=2, cfg=89))
+    for t0, t1 in ((-1, 2), (2, 1), (0, 4)):
+        assert B.cmn_allreduce_step_range(dc.plan.h, t0, t1, .1, .9, 0., 0) == B.CMN_EINVAL
+    assert B.cmn_allreduce_step(dc.plan.h, .1, .9, 0., 3) == B.CMN_EINVAL              # unknown destination
+    assert B.cmn_allreduce_adam_step(dc.plan.h, 1e-3, .9, .999, 1e-8, 0., 1, 0) == B.CMN_EUNBOUND   # no second moments
+    assert B.cmn_allreduce_step_range(dc.plan.h, 1, 1, .1, .9, 0., 0) == B.CMN_OK      # empty range: no-op
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_average_is_handed_back_to_every_replica(dtype, misalign):
+    """The all-gather half of the allreduce: afterwards every worker's gradient tensors hold the
+    average (rounded to nearest even when the workers store binary16)."""
+    import oracle
+    from paper_1710_11351_amd import binding as B
+    from parity_util import DeviceCase, assert_bit_equal, gen_all_grads
+    numel = [3000, 0, 77, 4096, 1, 2050]
+    c = wl.custom_config(numel, K=5, n_chunks=4, grad_dtype=dtype, cfg=88, outlier_frac=0.01 if dtype == "f16" else 0.0)
+    dc = DeviceCase(c, misalign=misalign)
+    p_o, v_o = [x.copy() for x in wl.gen_params(c)], wl.gen_velocity(c)
+    dc.set_state(p_o, v_o)
+    for step in range(2):
+        grads = gen_all_grads(c, step)
+        for k in range(c.K):
+            dc.set_grads(k, grads[k])
+        mean_o = oracle.allreduce_step(grads, p_o, v_o, c.n_chunks, c.lr, c.mu, c.wd, dtype=dtype)
+        dc.plan.allreduce_step(c.lr, c.mu, c.wd, mean_dest=B.CMN_MEAN_TO_ALL_REPLICAS)
+        want = [oracle.float_to_half(m) if dtype == "f16" else m for m in mean_o]
+        for k in range(c.K):
+            for t, (a, b) in enumerate(zip(dc.get(dc.grads[k]), want)):
+                assert_bit_equal(a, b, f"step {step} replica {k} tensor {t}")
+        for t, (a, b) in enumerate(zip(dc.get(dc.p) + dc.get(dc.v), p_o + v_o)):
+            assert_bit_equal(a, b, f"step {step} state {t}")
+
+
 # ---- the benchmark workloads at full size, in the launch configuration bench.py times ----
 def test_config3_resnet50_k32_full_size():
     run_parity(wl.config(3), steps=3)
@@ -127,3 +182,7 @@ def test_f16_storage_within_2e3_of_unquantised_fp32():
         want, mag = st.mean(axis=0), np.abs(st).mean(axis=0)
         assert np.all(np.abs(got[t] - want) <= 2e-3 * np.maximum(np.abs(want), mag)), f"tensor {t}"
         assert np.max(np.abs(got[t] - want)) > 0     # the quantisation is really there
+
+
+def test_config3_resnet50_k32_adam_full_size():
+    run_parity(wl.config(3), steps=2, opt="adam", staged=False)

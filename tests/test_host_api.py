@@ -126,7 +126,8 @@ def test_tile_table_covers_every_element_once_inside_one_chunk(dtype, rot):
     pp, base = _fake_ptrs(numel, base, 4)
     vp, base = _fake_ptrs(numel, base, 4)
     mp, base = _fake_ptrs(numel, base, 4)
-    rc, tiles = B.cmn_plan_describe_tiles(p.h, grads, pp, vp, mp)
+    sp, base = _fake_ptrs(numel, base, 4)
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, grads, pp, vp, mp, sp)
     assert rc == B.CMN_OK and len(tiles) == p.tile_count
     off = np.concatenate([[0], np.cumsum(numel)])
     covered = {t: 0 for t in range(len(numel))}
@@ -138,8 +139,9 @@ def test_tile_table_covers_every_element_once_inside_one_chunk(dtype, rot):
         assert c_first == c_last
         assert int(tl["start_rank"]) == (c_first % K if rot else 0)
         # all fake bases are 512-byte aligned, so the head only depends on e0
-        assert int(tl["head_step"]) == (-e0) % vec and int(tl["head_step_mean"]) == (-e0) % vec
-        assert int(tl["head_sgd"]) == (-e0) % 4
+        assert int(tl["head"][B.CMN_HEAD_STEP]) == (-e0) % vec and int(tl["head"][B.CMN_HEAD_STEP_MEAN]) == (-e0) % vec
+        assert int(tl["head"][B.CMN_HEAD_ADAM]) == (-e0) % vec and int(tl["head"][B.CMN_HEAD_ADAM_MEAN]) == (-e0) % vec
+        assert int(tl["head"][B.CMN_HEAD_SGD]) == (-e0) % 4 and int(tl["head"][B.CMN_HEAD_ADAM_OPT]) == (-e0) % 4
     assert [covered[t] for t in range(len(numel))] == numel
 
 
@@ -147,21 +149,40 @@ def test_tile_heads_follow_pointer_alignment():
     numel = [1000]
     p = B.Plan(numel, 2, 1)
     a = 1 << 20
+    H = lambda tiles, i: int(tiles[0]["head"][i])
     # both replicas, p and v start 3 elements past a 16-byte boundary: one leading element
     rc, tiles = B.cmn_plan_describe_tiles(p.h, [a + 12, 2 * a + 12], [3 * a + 12], [4 * a + 12], [5 * a + 12])
-    assert rc == 0 and [int(t["head_step"]) for t in tiles][0] == 1 and int(tiles[0]["head_sgd"]) == 1
+    assert rc == 0 and H(tiles, B.CMN_HEAD_STEP) == 1 and H(tiles, B.CMN_HEAD_SGD) == 1
+    assert H(tiles, B.CMN_HEAD_ADAM) == -1                       # no second moments given
     # replicas disagree: no common alignment
     rc, tiles = B.cmn_plan_describe_tiles(p.h, [a + 12, 2 * a + 8], [3 * a + 12], [4 * a + 12], [5 * a + 12])
-    assert rc == 0 and int(tiles[0]["head_step"]) == -1 and int(tiles[0]["head_sgd"]) == 1
+    assert rc == 0 and H(tiles, B.CMN_HEAD_STEP) == -1 and H(tiles, B.CMN_HEAD_SGD) == 1
     # mean gradient misaligned differently: only the variants that touch it lose the vector path
-    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a, 2 * a], [3 * a], [4 * a], [5 * a + 4])
-    assert rc == 0 and int(tiles[0]["head_step"]) == 0
-    assert int(tiles[0]["head_step_mean"]) == -1 and int(tiles[0]["head_sgd"]) == -1
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a, 2 * a], [3 * a], [4 * a], [5 * a + 4], [6 * a])
+    assert rc == 0 and H(tiles, B.CMN_HEAD_STEP) == 0 and H(tiles, B.CMN_HEAD_ADAM) == 0
+    assert H(tiles, B.CMN_HEAD_STEP_MEAN) == -1 and H(tiles, B.CMN_HEAD_SGD) == -1
+    assert H(tiles, B.CMN_HEAD_ADAM_MEAN) == -1 and H(tiles, B.CMN_HEAD_ADAM_OPT) == -1
+    # second moments misaligned: only Adam variants lose it
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a, 2 * a], [3 * a], [4 * a], [5 * a], [6 * a + 8])
+    assert rc == 0 and H(tiles, B.CMN_HEAD_STEP_MEAN) == 0 and H(tiles, B.CMN_HEAD_ADAM) == -1
     # unbound arrays
     rc, tiles = B.cmn_plan_describe_tiles(p.h, None, None, None, None)
-    assert rc == 0 and int(tiles[0]["head_step"]) == -1
+    assert rc == 0 and H(tiles, B.CMN_HEAD_STEP) == -1
     rc, _ = B.cmn_plan_describe_tiles(p.h, [a + 2, 2 * a], None, None, None)
     assert rc == B.CMN_EALIGN
+
+
+def test_range_and_adam_argument_checks():
+    p = B.Plan([100, 28, 7], 2, 2)
+    assert B.cmn_allreduce_step_range(None, 0, 1, .1, .9, 0., 0, 0) == B.CMN_ENULL
+    assert B.cmn_allreduce_step_range(p.h, 0, 1, .1, .9, 0., 0, 0) == B.CMN_EUNBOUND
+    assert B.cmn_allreduce_adam_step(p.h, 1e-3, .9, .999, 1e-8, 0., 0, 0, 0) == B.CMN_EINVAL      # t < 1
+    assert B.cmn_allreduce_adam_step(None, 1e-3, .9, .999, 1e-8, 0., 1, 0, 0) == B.CMN_ENULL
+    assert B.cmn_allreduce_adam_step(p.h, 1e-3, .9, .999, 1e-8, 0., 1, 0, 0) == B.CMN_EUNBOUND
+    assert B.cmn_adam(p.h, 1e-3, .9, .999, 1e-8, 0., 1, 0) == B.CMN_EUNBOUND
+    assert B.cmn_adam(p.h, 1e-3, .9, .999, 1e-8, 0., 0, 0) == B.CMN_EINVAL
+    assert B.cmn_plan_bind_adam(p.h, [1024, 2048, 4096], 0) == B.CMN_EUNBOUND                    # before cmn_plan_bind
+    assert B.cmn_plan_bind_adam(p.h, None, 0) == B.CMN_ENULL
 
 
 def test_empty_plans():
