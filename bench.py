@@ -31,12 +31,14 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(c, entry="step", write_mean=False):
+def algorithmic_bytes(c, entry="step", mean_dest=0, opt="sgd"):
     """Bytes the method must move per launch (padding, tables, scratch not counted)."""
     eg = 2 if c.grad_dtype == "f16" else 4
     N, K = c.N, c.K
+    state = 24 if opt == "adam" else 16                         # p + optimizer state, read and written
+    mean = {0: 0, 1: 4, 2: K * eg}[mean_dest]                   # averaged gradient written once / K times
     return {
-        "step": (K * eg + 16 + (4 if write_mean else 0)) * N,   # K grad reads, p v read, p v written
+        "step": (K * eg + state + mean) * N,
         "pack": 2 * K * eg * N,
         "ring_reduce": (K * eg + 4) * N,
         "scale_unpack": 8 * N,
@@ -70,7 +72,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
     ap.add_argument("--staged", action="store_true", help="also time the four staged entry points")
-    ap.add_argument("--write-mean", action="store_true", help="fused step also stores the mean gradient")
+    ap.add_argument("--mean-dest", type=int, default=0, choices=(0, 1, 2),
+                    help="0: mean gradient not stored; 1: stored once; 2: written back to all K replicas")
+    ap.add_argument("--opt", default="sgd", choices=("sgd", "adam"), help="optimizer fused into the step")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -108,13 +112,22 @@ def main():
     d_m = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in c.numel]
     plan = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype)
     plan.bind(d_g, d_p, d_v, d_m)
+    if args.opt == "adam":
+        d_s = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in c.numel]
+        plan.bind_adam(d_s)
+        it = [0]
+
+        def step():
+            it[0] += 1
+            plan.allreduce_adam_step(1e-3, 0.9, 0.999, 1e-8, c.wd, it[0], mean_dest=args.mean_dest)
+    else:
+        step = lambda: plan.allreduce_step(c.lr, c.mu, c.wd, mean_dest=args.mean_dest)
     torch.cuda.synchronize()
 
-    step = lambda: plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=args.write_mean)
     per, span_ms, wall_ms = time_launches(torch, step, args.steps, args.warmup)
     ms_per_step = span_ms / args.steps              # whole timed region / steps
     kern_ms = float(np.mean(per))                   # average duration of one launch
-    abytes = algorithmic_bytes(c, "step", args.write_mean)
+    abytes = algorithmic_bytes(c, "step", args.mean_dest, args.opt)
     value = abytes / (ms_per_step * 1e-3) / 1e9
     achieved = abytes / (kern_ms * 1e-3) / 1e9
     log(f"[bench] fused step: {ms_per_step * 1e3:.1f} us/step over {args.steps} steps "
@@ -148,7 +161,7 @@ def main():
     del src, dst, cal
 
     cpu = None
-    if not args.no_cpu:
+    if not args.no_cpu and (args.opt, args.mean_dest) == ("sgd", 0):
         import oracle                                # CPU baseline leg only
         threads = oracle.max_threads()
         p_o, v_o = [x.copy() for x in p_h], [x.copy() for x in v_h]
@@ -162,7 +175,7 @@ def main():
                "us_per_step": round(dt * 1e6, 1)}
         log(f"[bench] CPU oracle: {dt:.2f} s/step on {threads} threads -> {cpu['value']} GB/s effective")
 
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.config)
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.config) if (args.opt, args.mean_dest) == ("sgd", 0) else None
     out = {
         "metric": "effective HBM GB/s + us per ResNet-50 allreduce+update step at K=32" if args.config == 3
                   else f"effective HBM GB/s + us per allreduce+update step ({c.name})",
@@ -170,11 +183,12 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "us_per_step": round(ms_per_step * 1e3, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": c.name, "tensors": len(c.tensors), "elements": c.N, "replicas_K": c.K,
-                   "ring_chunks": c.n_chunks, "grad_storage": c.grad_dtype, "write_mean_grad": bool(args.write_mean),
-                   "entry": "cmn_allreduce_step"},
+                   "ring_chunks": c.n_chunks, "grad_storage": c.grad_dtype, "mean_dest": args.mean_dest,
+                   "optimizer": args.opt,
+                   "entry": "cmn_allreduce_adam_step" if args.opt == "adam" else "cmn_allreduce_step"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "k_allreduce_step", "algorithmic_bytes": abytes,
+                     "kernel": "k_step", "algorithmic_bytes": abytes,
                      "kernel_us": round(kern_ms * 1e3, 2), "device_copy_GBps": round(copy_gbps, 1)},
         "cpu_baseline": cpu,
     }
