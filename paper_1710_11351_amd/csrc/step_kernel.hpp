@@ -57,13 +57,6 @@ __global__ __launch_bounds__(kBlock) void k_step(
 
     for (int vi = threadIdx.x; vi < nvec; vi += kBlock) {
         const unsigned e = unsigned(head + vi * VEC);
-        f32x4 pv[VEC / 4], s1v[VEC / 4], s2v[VEC / 4];
-#pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            pv[q] = load_vec<f32x4>(p + e + 4 * q);
-            s1v[q] = load_vec<f32x4>(s1 + e + 4 * q);
-            if (ADAM) s2v[q] = load_vec<f32x4>(s2 + e + 4 * q);
-        }
         float gb[VEC];
         if (SRC == SRC_MEAN) {
             const f32x4 g = load_vec<f32x4>(m + e);
@@ -85,6 +78,14 @@ __global__ __launch_bounds__(kBlock) void k_step(
                 G::accumulate(gb, load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e));
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
+        }
+        // parameter and state are fetched only now, close to the stores that rewrite them
+        f32x4 pv[VEC / 4], s1v[VEC / 4], s2v[VEC / 4];
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            pv[q] = load_vec<f32x4>(p + e + 4 * q);
+            s1v[q] = load_vec<f32x4>(s1 + e + 4 * q);
+            if (ADAM) s2v[q] = load_vec<f32x4>(s2 + e + 4 * q);
         }
 
 #pragma unroll
