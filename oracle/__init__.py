@@ -18,9 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cmn_oracle.c")
 _LIB = os.path.join(_HERE, "libcmn_oracle.so")
 
-F32, F16 = 0, 1
-_DT = {"f32": F32, "f16": F16, F32: F32, F16: F16}
-_NP = {F32: np.float32, F16: np.float16}
+F32, F16, BF16 = 0, 1, 2
+_DT = {"f32": F32, "f16": F16, "bf16": BF16, F32: F32, F16: F16, BF16: BF16}
+_NP = {F32: np.float32, F16: np.float16, BF16: np.uint16}     # bfloat16 travels as raw 16-bit patterns
 
 
 def build(force: bool = False) -> str:
@@ -62,6 +62,12 @@ def lib() -> ctypes.CDLL:
         L.orc_momentum_sgd.restype = None
         L.orc_momentum_sgd.argtypes = [ctypes.c_int64, fp, fp, fp, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_float]
+        L.orc_bf16_bits_to_float.restype = ctypes.c_float
+        L.orc_bf16_bits_to_float.argtypes = [ctypes.c_uint16]
+        L.orc_float_to_bf16_bits.restype = ctypes.c_uint16
+        L.orc_float_to_bf16_bits.argtypes = [ctypes.c_float]
+        L.orc_float_to_bf16_array.restype = None
+        L.orc_float_to_bf16_array.argtypes = [ctypes.c_int64, fp, ctypes.c_void_p]
         L.orc_float_to_half_bits.restype = ctypes.c_uint16
         L.orc_float_to_half_bits.argtypes = [ctypes.c_float]
         L.orc_float_to_half_array.restype = None
@@ -189,6 +195,18 @@ def float_to_half(a: np.ndarray) -> np.ndarray:
     out = np.empty(a.shape, dtype=np.uint16)
     lib().orc_float_to_half_array(a.size, _fp(a.reshape(-1)), out.ctypes.data)
     return out.view(np.float16)
+
+
+def float_to_bf16(a: np.ndarray) -> np.ndarray:
+    """binary32 -> bfloat16 bit patterns (uint16), round to nearest even."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.uint16)
+    lib().orc_float_to_bf16_array(a.size, _fp(a.reshape(-1)), out.ctypes.data)
+    return out
+
+
+def bf16_bits_to_float(b: int) -> np.float32:
+    return np.float32(lib().orc_bf16_bits_to_float(int(b) & 0xFFFF))
 
 
 def adam_lr(alpha: float, beta1: float, beta2: float, t: int) -> float:

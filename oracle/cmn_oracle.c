@@ -21,8 +21,9 @@
  * plain rule theta - lr*g at mu = 0, torch.optim.SGD, and an exhaustive
  * binary16 decode against numpy.  No function here is "parity unpinned".
  *
- * dtype codes: 0 = float32 gradients, 1 = IEEE binary16 gradients (storage
- * only; every sum is accumulated in float32).
+ * dtype codes: 0 = float32 gradients, 1 = IEEE binary16 gradients, 2 = bfloat16
+ * gradients (the upper 16 bits of a binary32).  16-bit types are storage only;
+ * every sum is accumulated in float32.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -31,6 +32,7 @@
 
 #define ORC_F32 0
 #define ORC_F16 1
+#define ORC_BF16 2
 
 /* ---- binary16 -> binary32, bit level (exact, incl. subnormals, Inf, NaN) ---- */
 float orc_half_bits_to_float(uint16_t h)
@@ -54,14 +56,40 @@ float orc_half_bits_to_float(uint16_t h)
     return f;
 }
 
+/* ---- bfloat16 <-> binary32: a bfloat16 is the sign, exponent and top 7 mantissa bits ---- */
+float orc_bf16_bits_to_float(uint16_t b)
+{
+    uint32_t bits = (uint32_t)b << 16;   /* exact: the dropped mantissa bits are zero */
+    float f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+uint16_t orc_float_to_bf16_bits(float f)      /* round to nearest, ties to even */
+{
+    uint32_t x;
+    memcpy(&x, &f, 4);
+    if ((x & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x >> 16) | 0x0040u);   /* NaN stays NaN (quiet) */
+    uint32_t kept = x >> 16, rem = x & 0xffffu;
+    if (rem > 0x8000u || (rem == 0x8000u && (kept & 1u))) ++kept;   /* a carry into the exponent, or to Inf, is correct */
+    return (uint16_t)kept;
+}
+
+void orc_float_to_bf16_array(int64_t n, const float *in, uint16_t *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = orc_float_to_bf16_bits(in[i]);
+}
+
 static float load_grad(const void *base, int dtype, int64_t i)
 {
     if (dtype == ORC_F16)
         return orc_half_bits_to_float(((const uint16_t *)base)[i]);
+    if (dtype == ORC_BF16)
+        return orc_bf16_bits_to_float(((const uint16_t *)base)[i]);
     return ((const float *)base)[i];
 }
 
-static int elem_bytes(int dtype) { return dtype == ORC_F16 ? 2 : 4; }
+static int elem_bytes(int dtype) { return dtype == ORC_F32 ? 4 : 2; }
 
 /* ---- geometry of the packed buffer ------------------------------------------
  * off[0] = 0, off[t+1] = off[t] + numel[t], N = off[T].

@@ -39,6 +39,10 @@ MUTANTS = [
     ("encode_subnormal_truncates", "if (rem > half || (rem == half && (q & 1u))) ++q;", "(void)rem; (void)half;"),
     ("encode_flushes_subnormals", "if (e < -10) return sign;", "if (e <= 0) return sign;"),
     ("encode_saturates_instead_of_inf", "if (e >= 31) return (uint16_t)(sign | 0x7c00u);", "if (e >= 31) return (uint16_t)(sign | 0x7bffu);"),
+    ("bf16_decode_shift", "uint32_t bits = (uint32_t)b << 16;", "uint32_t bits = (uint32_t)b << 15;"),
+    ("bf16_encode_truncates", "if (rem > 0x8000u || (rem == 0x8000u && (kept & 1u))) ++kept;", "(void)rem;"),
+    ("bf16_encode_ties_away", "(rem == 0x8000u && (kept & 1u))) ++kept;", "(rem == 0x8000u)) ++kept;"),
+    ("bf16_nan_becomes_inf", "return (uint16_t)((x >> 16) | 0x0040u);", "return (uint16_t)(x >> 16);"),
     ("adam_first_moment_no_decay", "float mn = m[i] + t2;", "float mn = m[i] + t1;"),
     ("adam_second_moment_uses_g", "float t3 = gi * gi;", "float t3 = gi;"),
     ("adam_eps_inside_sqrt", "float s = sqrtf(vn);\n        float den = s + eps;", "float s = sqrtf(vn + eps);\n        float den = s;"),

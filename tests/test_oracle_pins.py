@@ -453,3 +453,42 @@ def test_adam_lr_closed_form():
     for t in (1, 2, 10, 1000):
         want = np.float64(np.float32(1e-3)) * np.sqrt(1 - np.float64(np.float32(0.999)) ** t) / (1 - np.float64(np.float32(0.9)) ** t)
         assert oracle.adam_lr(1e-3, 0.9, 0.999, t) == np.float32(want)
+
+
+# ------------------------------------------------------------------ bfloat16
+def test_bf16_decode_exhaustive_against_torch():
+    import torch
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    want = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).float().numpy()
+    got = np.array([oracle.bf16_bits_to_float(int(b)) for b in bits], dtype=np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    assert np.array_equal(got[~nan].view(np.uint32), bits[~nan].astype(np.uint32) << 16)
+
+
+def test_bf16_encode_against_torch_on_edges_and_random_patterns():
+    import torch
+    rng = np.random.default_rng(31)
+    every = (np.arange(65536, dtype=np.uint32) << 16).view(np.float32)        # every bfloat16 value
+    every = every[np.isfinite(every)]
+    ties = ((np.arange(65536, dtype=np.uint32) << 16) | 0x8000).view(np.float32)   # exact midpoints
+    near = np.concatenate([np.nextafter(ties, np.float32(np.inf)), np.nextafter(ties, np.float32(-np.inf))])
+    rand = rng.integers(0, 2 ** 32, 4_000_000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    x = np.concatenate([every, ties, near, rand, np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 3.4e38, -3.4e38, 1e-45], np.float32)])
+    got = oracle.float_to_bf16(x)
+    want = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    nan = np.isnan(x)
+    assert np.all((got[nan] & 0x7f80) == 0x7f80) and np.all((got[nan] & 0x7f) != 0)      # NaN stays NaN
+    assert np.array_equal(got[~nan], want[~nan])
+
+
+def test_bf16_storage_fold_equals_fold_of_decoded_values():
+    rng = np.random.default_rng(32)
+    K, ce = 4, 128
+    b = [oracle.float_to_bf16((rng.standard_normal(K * ce) * 1e-3).astype(np.float32)) for _ in range(K)]
+    gb = oracle.Geometry([K * ce], K, 256, "bf16")
+    g32 = oracle.Geometry([K * ce], K, 256, "f32")
+    assert gb.chunk_elems == g32.chunk_elems == ce
+    dec = [(x.astype(np.uint32) << 16).view(np.float32) for x in b]
+    assert np.array_equal(oracle.direct_fold(gb, b).view(np.uint32), oracle.direct_fold(g32, dec).view(np.uint32))
