@@ -59,7 +59,8 @@ enum cmn_status {
 
 enum cmn_dtype {
     CMN_F32 = 0, /* gradients stored as IEEE binary32 */
-    CMN_F16 = 1  /* gradients stored as IEEE binary16, decoded exactly and summed in binary32 */
+    CMN_F16 = 1, /* gradients stored as IEEE binary16, decoded exactly and summed in binary32 */
+    CMN_BF16 = 2 /* gradients stored as bfloat16 (upper half of a binary32), same treatment   */
 };
 
 /* Where a fused step puts the averaged gradient. */
@@ -68,7 +69,7 @@ enum cmn_mean_dest {
     CMN_MEAN_TO_MEAN_GRADS = 1,   /* into the bound mean_grad_ptrs (float32)                   */
     CMN_MEAN_TO_ALL_REPLICAS = 2  /* over every replica's own gradient tensors, i.e. the
                                      "every worker receives the average" half of an allreduce;
-                                     rounded to nearest even when gradients are binary16      */
+                                     rounded to nearest even when gradients are 16-bit        */
 };
 
 /* Which streams a kernel variant touches; index into cmn_tile.head. */

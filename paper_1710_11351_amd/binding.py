@@ -18,8 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcmn.so")
 
 CMN_OK, CMN_EINVAL, CMN_ENULL, CMN_ESIZE, CMN_EALIGN, CMN_EUNBOUND, CMN_EHIP, CMN_ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
-CMN_F32, CMN_F16 = 0, 1
-_DT = {"f32": CMN_F32, "f16": CMN_F16, CMN_F32: CMN_F32, CMN_F16: CMN_F16}
+CMN_F32, CMN_F16, CMN_BF16 = 0, 1, 2
+_DT = {"f32": CMN_F32, "f16": CMN_F16, "bf16": CMN_BF16, CMN_F32: CMN_F32, CMN_F16: CMN_F16, CMN_BF16: CMN_BF16}
 
 
 CMN_MEAN_NONE, CMN_MEAN_TO_MEAN_GRADS, CMN_MEAN_TO_ALL_REPLICAS = 0, 1, 2

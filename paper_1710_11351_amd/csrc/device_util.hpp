@@ -17,6 +17,7 @@ namespace cmn {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
 // Storage traits of the gradient element type.
 template <int DT> struct GradT;
@@ -51,6 +52,30 @@ template <> struct GradT<CMN_F16> {
     }
 };
 
+template <> struct GradT<CMN_BF16> {
+    using elem = unsigned short;        // raw bfloat16 bit pattern
+    using raw = u16x8;
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float decode(elem x) {
+        return __builtin_bit_cast(float, static_cast<unsigned>(x) << 16);   // exact
+    }
+    static __device__ __forceinline__ elem encode(float x) {                 // nearest, ties to even
+        const unsigned u = __builtin_bit_cast(unsigned, x);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<elem>((u >> 16) | 0x40u);   // NaN stays NaN
+        return static_cast<elem>((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    }
+    static __device__ __forceinline__ void accumulate(float (&acc)[8], const raw &r) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = acc[i] + decode(r[i]);
+    }
+    static __device__ __forceinline__ raw encode_vec(const float (&g)[8]) {
+        raw r;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = encode(g[i]);
+        return r;
+    }
+};
+
 template <typename V>
 __device__ __forceinline__ V load_vec(const void *p) {
     return *reinterpret_cast<const V *>(p);
@@ -80,6 +105,9 @@ __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned
 }
 
 __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f16x8 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
+}
+__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, u16x8 v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
 }
 

@@ -137,7 +137,7 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
     *out = nullptr;
     if (n_tensors < 0 || K < 1 || n_chunks < 1) return CMN_EINVAL;
     if (n_tensors > 0 && !numel) return CMN_ENULL;
-    if (grad_dtype != CMN_F32 && grad_dtype != CMN_F16) return CMN_EINVAL;
+    if (grad_dtype != CMN_F32 && grad_dtype != CMN_F16 && grad_dtype != CMN_BF16) return CMN_EINVAL;
     if (ring_rotate != 0 && ring_rotate != 1) return CMN_EINVAL;
     if (align_bytes < 16 || (align_bytes & (align_bytes - 1)) != 0) return CMN_EINVAL;
     if (n_tensors > kMaxTensors || K > kMaxReplicas || align_bytes > (1 << 20)) return CMN_ESIZE;

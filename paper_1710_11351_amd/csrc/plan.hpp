@@ -17,7 +17,7 @@ constexpr int kBlock = 256;  // threads per workgroup of every kernel (4 wavefro
 // Elements of one cmn_tile at most: kBlock threads x one 16-byte vector x kTileIters.
 constexpr int kTileIters = 1;
 
-inline int elem_bytes(int dtype) { return dtype == CMN_F16 ? 2 : 4; }
+inline int elem_bytes(int dtype) { return dtype == CMN_F32 ? 4 : 2; }
 inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }
 
 // Byte offsets of the tables inside the caller's device workspace (each 256-aligned).

@@ -71,11 +71,12 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
     if (tpc * plan->C > 0x7fffffffLL) return CMN_ESIZE;
     const dim3 grid(unsigned(tpc * plan->C));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (plan->dtype == CMN_F32)
-        hipLaunchKernelGGL((k_ring_reduce<CMN_F32, 16>), grid, dim3(kBlock), 0, s, packed, reduced,
-                           (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate);
-    else
-        hipLaunchKernelGGL((k_ring_reduce<CMN_F16, 16>), grid, dim3(kBlock), 0, s, packed, reduced,
-                           (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate);
+#define CMN_LAUNCH_REDUCE(DT)                                                                              \
+    hipLaunchKernelGGL((k_ring_reduce<DT, 16>), grid, dim3(kBlock), 0, s, packed, reduced, (long long)plan->L, \
+                       (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate)
+    if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE(CMN_F32);
+    else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE(CMN_F16);
+    else CMN_LAUNCH_REDUCE(CMN_BF16);
+#undef CMN_LAUNCH_REDUCE
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }

@@ -163,15 +163,16 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     if (n == 0) return CMN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CMN_STEP_CASE(DT, MEAN) launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s)
-    if (plan->dtype == CMN_F32) {
-        if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(CMN_F32, CMN_MEAN_NONE);
-        else if (mean_dest == CMN_MEAN_TO_MEAN_GRADS) CMN_STEP_CASE(CMN_F32, CMN_MEAN_TO_MEAN_GRADS);
-        else CMN_STEP_CASE(CMN_F32, CMN_MEAN_TO_ALL_REPLICAS);
-    } else {
-        if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(CMN_F16, CMN_MEAN_NONE);
-        else if (mean_dest == CMN_MEAN_TO_MEAN_GRADS) CMN_STEP_CASE(CMN_F16, CMN_MEAN_TO_MEAN_GRADS);
-        else CMN_STEP_CASE(CMN_F16, CMN_MEAN_TO_ALL_REPLICAS);
-    }
+#define CMN_STEP_DTYPE(DT)                                                                  \
+    do {                                                                                    \
+        if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(DT, CMN_MEAN_NONE);                   \
+        else if (mean_dest == CMN_MEAN_TO_MEAN_GRADS) CMN_STEP_CASE(DT, CMN_MEAN_TO_MEAN_GRADS); \
+        else CMN_STEP_CASE(DT, CMN_MEAN_TO_ALL_REPLICAS);                                   \
+    } while (0)
+    if (plan->dtype == CMN_F32) CMN_STEP_DTYPE(CMN_F32);
+    else if (plan->dtype == CMN_F16) CMN_STEP_DTYPE(CMN_F16);
+    else CMN_STEP_DTYPE(CMN_BF16);
+#undef CMN_STEP_DTYPE
 #undef CMN_STEP_CASE
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }

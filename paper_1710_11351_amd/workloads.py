@@ -100,7 +100,7 @@ class Config:
     tensors: Tuple[TensorSpec, ...]
     K: int            # worker replicas
     n_chunks: int     # ring chunks
-    grad_dtype: str   # "f32" | "f16"  (storage type of gradients)
+    grad_dtype: str   # "f32" | "f16" | "bf16"  (storage type of gradients; bf16 as uint16 bit patterns)
     grad_std: float
     per_layer_fan_in_scale: bool
     outlier_frac: float
@@ -163,6 +163,12 @@ def _split(flat: np.ndarray, numel: Sequence[int]) -> List[np.ndarray]:
     return out
 
 
+def _bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Quantise finite float32 inputs to bfloat16 bit patterns (nearest, ties to even)."""
+    u = x.view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
 def gen_grads(c: Config, step: int, k: int) -> List[np.ndarray]:
     """Replica ``k``'s per-layer gradients for iteration ``step`` (list of 1-D
     arrays in list order; dtype float32 or float16 per ``c.grad_dtype``)."""
@@ -179,6 +185,8 @@ def gen_grads(c: Config, step: int, k: int) -> List[np.ndarray]:
         flat[mask] *= np.float32(c.outlier_scale)
     if c.grad_dtype == "f16":
         return _split(flat.astype(np.float16), numel)  # round-to-nearest-even
+    if c.grad_dtype == "bf16":
+        return _split(_bf16_bits(flat), numel)         # uint16 bit patterns
     return _split(flat, numel)
 
 

@@ -11,6 +11,8 @@ from paper_1710_11351_amd import workloads as wl
 
 def bits(a):
     a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return a
     return a.view(np.uint16 if a.dtype == np.float16 else np.uint32)
 
 
@@ -35,14 +37,20 @@ def assert_update_close(got, want, what, rel=1e-6):
     assert np.all(err <= 0), f"{what}: exceeds {rel} relative by {err.max()}"
 
 
+def to_numpy(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
 class DeviceCase:
     """Device tensors of one workload, each tensor its own allocation."""
 
     def __init__(self, c: wl.Config, ring_rotate=1, misalign=0, with_mean=True, adam=False):
         import torch
         self.c, self.torch = c, torch
-        self.np_g = np.float16 if c.grad_dtype == "f16" else np.float32
-        tg = torch.float16 if c.grad_dtype == "f16" else torch.float32
+        tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[c.grad_dtype]
         self.plan = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype, ring_rotate)
 
         def alloc(dtype):
@@ -69,11 +77,15 @@ class DeviceCase:
 
     def set_grads(self, k, g_host):
         for d, h in zip(self.grads[k], g_host):
-            d.copy_(self.torch.from_numpy(np.ascontiguousarray(h)))
+            h = np.ascontiguousarray(h)
+            if h.dtype == np.uint16:                       # bfloat16 bit patterns
+                d.copy_(self.torch.from_numpy(h.view(np.int16)).view(self.torch.bfloat16))
+            else:
+                d.copy_(self.torch.from_numpy(h))
 
     def get(self, tensors):
         self.torch.cuda.synchronize()
-        return [t.cpu().numpy() for t in tensors]
+        return [to_numpy(t) for t in tensors]
 
 
 def gen_all_grads(c: wl.Config, step: int, unquantised=False):
@@ -108,7 +120,7 @@ def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fu
     geo = oracle.Geometry(c.numel, c.n_chunks, c.align_bytes, c.grad_dtype)
     if staged:
         dc = cases["staged"]
-        tg = torch.float16 if c.grad_dtype == "f16" else torch.float32
+        tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[c.grad_dtype]
         packed = torch.full((c.K * geo.L + 64,), 7.0, dtype=tg, device="cuda")[: c.K * geo.L]
         reduced = torch.full((geo.L + 64,), 7.0, dtype=torch.float32, device="cuda")[: geo.L]
         assert dc.plan.L == geo.L
@@ -136,7 +148,7 @@ def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fu
             if check_packed and (step == 0 or c.K * geo.L < 50_000_000):
                 torch.cuda.synchronize()
                 for k in range(c.K):
-                    assert_bit_equal(packed[k * geo.L:(k + 1) * geo.L].cpu().numpy(), packed_o[k],
+                    assert_bit_equal(to_numpy(packed[k * geo.L:(k + 1) * geo.L]), packed_o[k],
                                      f"step {step} packed[{k}]")
             dc.plan.ring_reduce(packed, reduced)
             torch.cuda.synchronize()

@@ -13,7 +13,7 @@ def test_config1_mlp_k2():
 
 
 @pytest.mark.parametrize("rot", [0, 1])
-@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 def test_ragged_list_with_empty_tensors(dtype, rot):
     # odd sizes, empty tensors, tiles and vectors that straddle tensor and chunk edges, K not a power of two
     numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3]
@@ -22,7 +22,7 @@ def test_ragged_list_with_empty_tensors(dtype, rot):
     run_parity(c, steps=3, ring_rotate=rot)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("misalign", [1, 3])
 def test_unaligned_base_pointers(dtype, misalign):
     c = wl.custom_config([1000, 4096, 37, 8192 + 5], K=4, n_chunks=4, grad_dtype=dtype, cfg=92)
@@ -47,6 +47,35 @@ def test_more_chunks_than_replicas_and_k7():
 def test_many_replicas_f16_k40():
     c = wl.custom_config([20000, 1000, 24], K=40, n_chunks=40, grad_dtype="f16", cfg=96, outlier_frac=0.01)
     run_parity(c, steps=2)
+
+
+def test_bf16_storage_adam_k33():
+    c = wl.custom_config([20000, 1000, 24, 4096], K=33, n_chunks=11, grad_dtype="bf16", cfg=86)
+    run_parity(c, steps=2, opt="adam")
+
+
+def test_bf16_storage_within_8e3_of_unquantised_fp32():
+    """bfloat16 keeps 8 significant bits: rounding moves an element by at most 2^-9 = 1.95e-3 of its
+    magnitude, so the mean moves by at most 1.95e-3 * mean_k |g_k|; asserted with the bar 8e-3 / 2 = 4e-3."""
+    import torch
+    from paper_1710_11351_amd import binding as B
+    from parity_util import gen_all_grads, to_numpy
+    numel = [36864, 64, 147456, 1000]
+    c = wl.custom_config(numel, K=16, n_chunks=16, grad_dtype="bf16", cfg=85, grad_std=1e-3)
+    gq = gen_all_grads(c, 0)
+    g32 = gen_all_grads(c, 0, unquantised=True)
+    d_g = [[torch.from_numpy(h.view(np.int16).copy()).view(torch.bfloat16).cuda() for h in g] for g in gq]
+    d_p = B.upload_tensors(wl.gen_params(c)); d_v = B.upload_tensors(wl.gen_velocity(c))
+    d_m = [torch.zeros(n, device="cuda") for n in numel]
+    plan = B.Plan(numel, c.K, c.n_chunks, 256, "bf16")
+    plan.bind(d_g, d_p, d_v, d_m)
+    plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=True)
+    got = B.download_tensors(d_m)
+    for t in range(len(numel)):
+        st = np.stack([g[t].astype(np.float64) for g in g32])
+        want, mag = st.mean(axis=0), np.abs(st).mean(axis=0)
+        assert np.all(np.abs(got[t] - want) <= 4e-3 * np.maximum(np.abs(want), mag)), f"tensor {t}"
+        assert np.max(np.abs(got[t] - want)) > 0
 
 
 def test_special_values_propagate():
@@ -114,7 +143,7 @@ def test_range_arguments_are_validated():
     assert B.cmn_allreduce_step_range(dc.plan.h, 1, 1, .1, .9, 0., 0) == B.CMN_OK      # empty range: no-op
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("misalign", [0, 1])
 def test_average_is_handed_back_to_every_replica(dtype, misalign):
     """The all-gather half of the allreduce: afterwards every worker's gradient tensors hold the
@@ -133,7 +162,7 @@ def test_average_is_handed_back_to_every_replica(dtype, misalign):
             dc.set_grads(k, grads[k])
         mean_o = oracle.allreduce_step(grads, p_o, v_o, c.n_chunks, c.lr, c.mu, c.wd, dtype=dtype)
         dc.plan.allreduce_step(c.lr, c.mu, c.wd, mean_dest=B.CMN_MEAN_TO_ALL_REPLICAS)
-        want = [oracle.float_to_half(m) if dtype == "f16" else m for m in mean_o]
+        want = [{"f16": oracle.float_to_half, "bf16": oracle.float_to_bf16, "f32": lambda x: x}[dtype](m) for m in mean_o]
         for k in range(c.K):
             for t, (a, b) in enumerate(zip(dc.get(dc.grads[k]), want)):
                 assert_bit_equal(a, b, f"step {step} replica {k} tensor {t}")
