@@ -121,6 +121,30 @@ __device__ __forceinline__ int ring_rank(int s, int j, int K) {
     return r >= K ? r - K : r;
 }
 
+// Fold replicas [j, j + B) of the fixed order into acc: B vector loads are issued back to
+// back, then added strictly in order.  ptr_of(j) yields the address of replica j's vector.
+template <int DT, int B, typename PtrFn>
+__device__ __forceinline__ void fold_batch(float (&acc)[GradT<DT>::VEC], int j, PtrFn ptr_of) {
+    using G = GradT<DT>;
+    typename G::raw g[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u) g[u] = load_stream<typename G::raw>(ptr_of(j + u));
+#pragma unroll
+    for (int u = 0; u < B; ++u) G::accumulate(acc, g[u]);
+}
+
+// The whole K-term fold: batches of U, then the remainder in halving batches so that a K
+// that is not a multiple of U still keeps several loads in flight.
+template <int DT, int U, typename PtrFn>
+__device__ __forceinline__ void fold_all(float (&acc)[GradT<DT>::VEC], int K, PtrFn ptr_of) {
+    int j = 0;
+    for (; j + U <= K; j += U) fold_batch<DT, U>(acc, j, ptr_of);
+    if (U > 8 && j + 8 <= K) { fold_batch<DT, 8>(acc, j, ptr_of); j += 8; }
+    if (U > 4 && j + 4 <= K) { fold_batch<DT, 4>(acc, j, ptr_of); j += 4; }
+    if (U > 2 && j + 2 <= K) { fold_batch<DT, 2>(acc, j, ptr_of); j += 2; }
+    if (j < K) fold_batch<DT, 1>(acc, j, ptr_of);
+}
+
 // Optimizer hyper-parameters as the kernels receive them (by value).
 //   MomentumSGD: a = lr, b = mu.        Adam: a = lr_t, b = 1 - beta1, c = 1 - beta2, d = eps.
 struct OptArgs {

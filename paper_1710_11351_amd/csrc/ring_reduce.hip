@@ -38,15 +38,7 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
-        int j = 0;
-        for (; j + U <= K; j += U) {
-            raw g[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) g[u] = load_stream<raw>(src + (long long)ring_rank(s, j + u, K) * L + e);
-#pragma unroll
-            for (int u = 0; u < U; ++u) G::accumulate(acc, g[u]);
-        }
-        for (; j < K; ++j) G::accumulate(acc, load_stream<raw>(src + (long long)ring_rank(s, j, K) * L + e));
+        fold_all<DT, U>(acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; });
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
             f32x4 o;

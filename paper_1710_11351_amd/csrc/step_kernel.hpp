@@ -65,17 +65,9 @@ __global__ __launch_bounds__(kBlock) void k_step(
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
-            int j = 0;
-            for (; j + U <= K; j += U) {
-                raw g[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    g[u] = load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j + u, K)]) + tl.e0 + e);
-#pragma unroll
-                for (int u = 0; u < U; ++u) G::accumulate(gb, g[u]);
-            }
-            for (; j < K; ++j)
-                G::accumulate(gb, load_stream<raw>(static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e));
+            fold_all<DT, U>(gb, K, [&](int j) {
+                return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e;
+            });
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
         }
