@@ -190,3 +190,15 @@ def test_empty_plans():
         p = B.Plan(numel, 4, 4)
         assert (p.N, p.L, p.chunk_elems, p.tile_count) == (0, 0, 0, 0)
         assert p.workspace_bytes >= 256
+
+
+def test_plain_c_client_links_and_runs(tmp_path):
+    """include/cmn.h compiles as C11 and a C program can drive the library with no C++/Python."""
+    import subprocess
+    exe = tmp_path / "abi_check"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "abi_check.c"), "-o", str(exe), "-L", libdir, "-lcmn",
+                    f"-Wl,-rpath,{libdir}"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and "abi_check ok" in r.stdout, r.stdout + r.stderr
