@@ -261,3 +261,40 @@ def test_range_steps_replayed_from_a_hip_graph_match_eager():
         for name in ("p", "v", "m"):
             for t, (a, b) in enumerate(zip(graphed.get(getattr(graphed, name)), eager.get(getattr(eager, name)))):
                 assert_bit_equal(a, b, f"replay {step} {name}[{t}]")
+
+
+def test_very_long_tensor_list_uses_the_global_memory_tables():
+    """More tensors than the LDS copy of the offsets and pointer tables can hold (3071): pack and
+    unpack search the tables in global memory instead; results must not change."""
+    rng = np.random.default_rng(5)
+    numel = [int(x) for x in rng.integers(0, 9, 5000)] + [4096, 3]
+    c = wl.custom_config(numel, K=3, n_chunks=4, cfg=84)
+    run_parity(c, steps=1)
+    c16 = wl.custom_config(numel[:4000], K=2, n_chunks=3, grad_dtype="f16", cfg=83)
+    run_parity(c16, steps=1)
+
+
+def test_buffer_arguments_are_validated_on_a_bound_plan():
+    import torch
+    from paper_1710_11351_amd import binding as B
+    from parity_util import DeviceCase
+    dc = DeviceCase(wl.custom_config([1000, 24], K=2, n_chunks=2, cfg=82))
+    L = dc.plan.L
+    packed = torch.zeros(2 * L + 64, device="cuda")
+    reduced = torch.zeros(L + 64, device="cuda")
+    assert B.cmn_pack(dc.plan.h, None) == B.CMN_ENULL
+    assert B.cmn_pack(dc.plan.h, packed.data_ptr() + 4) == B.CMN_EALIGN
+    assert B.cmn_ring_reduce(dc.plan.h, packed.data_ptr(), reduced.data_ptr() + 16) == B.CMN_EALIGN
+    assert B.cmn_scale_unpack(dc.plan.h, None) == B.CMN_ENULL
+    assert B.cmn_scale_unpack(dc.plan.h, reduced.data_ptr() + 128) == B.CMN_EALIGN
+    assert B.cmn_pack(dc.plan.h, packed) == B.CMN_OK
+    assert B.cmn_ring_reduce(dc.plan.h, packed, reduced) == B.CMN_OK
+    assert B.cmn_scale_unpack(dc.plan.h, reduced) == B.CMN_OK
+    torch.cuda.synchronize()
+    # a plan bound without mean gradients refuses the entry points that need them
+    dc2 = DeviceCase(wl.custom_config([1000, 24], K=2, n_chunks=2, cfg=82), with_mean=False)
+    assert B.cmn_scale_unpack(dc2.plan.h, reduced) == B.CMN_EUNBOUND
+    assert B.cmn_momentum_sgd(dc2.plan.h, .1, .9, 0.) == B.CMN_EUNBOUND
+    assert B.cmn_allreduce_step(dc2.plan.h, .1, .9, 0., B.CMN_MEAN_TO_MEAN_GRADS) == B.CMN_EUNBOUND
+    assert B.cmn_allreduce_step(dc2.plan.h, .1, .9, 0., B.CMN_MEAN_NONE) == B.CMN_OK
+    torch.cuda.synchronize()
