@@ -18,9 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cmn_oracle.c")
 _LIB = os.path.join(_HERE, "libcmn_oracle.so")
 
-F32, F16, BF16 = 0, 1, 2
-_DT = {"f32": F32, "f16": F16, "bf16": BF16, F32: F32, F16: F16, BF16: BF16}
-_NP = {F32: np.float32, F16: np.float16, BF16: np.uint16}     # bfloat16 travels as raw 16-bit patterns
+F32, F16, BF16, I8S = 0, 1, 2, 3
+_DT = {"f32": F32, "f16": F16, "bf16": BF16, "i8s": I8S, F32: F32, F16: F16, BF16: BF16, I8S: I8S}
+_NP = {F32: np.float32, F16: np.float16, BF16: np.uint16, I8S: np.int8}   # bfloat16 travels as raw 16-bit patterns
 
 
 def build(force: bool = False) -> str:
@@ -52,7 +52,7 @@ def lib() -> ctypes.CDLL:
         L.orc_pack.argtypes = [ctypes.c_int, i64p, vpp, ctypes.c_int, ctypes.c_int64, ctypes.c_void_p]
         L.orc_direct_fold.restype = None
         L.orc_direct_fold.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, vpp, ctypes.c_int,
-                                      ctypes.c_int, fp]
+                                      ctypes.c_int, vpp, fp]
         L.orc_ring_allreduce.restype = ctypes.c_int
         L.orc_ring_allreduce.argtypes = [ctypes.c_int, ctypes.c_int64, vpp]
         L.orc_scale.restype = None
@@ -139,13 +139,20 @@ def pack(geo: Geometry, tensors: Sequence[np.ndarray]) -> np.ndarray:
     return out
 
 
-def direct_fold(geo: Geometry, packed: Sequence[np.ndarray], ring_rotate: int = 1) -> np.ndarray:
-    """S2 by definition: K packed buffers -> float32 sum[L], fixed fold order."""
+def direct_fold(geo: Geometry, packed: Sequence[np.ndarray], ring_rotate: int = 1,
+                scales: Sequence[np.ndarray] = None) -> np.ndarray:
+    """S2 by definition: K packed buffers -> float32 sum[L], fixed fold order.
+    scales[k] (float32, one per ring chunk) is required for int8 storage."""
     K = len(packed)
     for b in packed:
         assert b.dtype == _NP[geo.dtype] and b.size == geo.L
+    assert (scales is not None) == (geo.dtype == I8S)
+    if scales is not None:
+        scales = [np.ascontiguousarray(s, dtype=np.float32) for s in scales]
+        assert len(scales) == K and all(s.size == geo.C for s in scales)
     out = np.empty(geo.L, dtype=np.float32)
-    lib().orc_direct_fold(K, geo.C, geo.chunk_elems, _ptrs(packed), geo.dtype, int(ring_rotate), _fp(out))
+    lib().orc_direct_fold(K, geo.C, geo.chunk_elems, _ptrs(packed), geo.dtype, int(ring_rotate),
+                          _ptrs(scales) if scales is not None else None, _fp(out))
     return out
 
 
@@ -222,24 +229,24 @@ def adam(g: np.ndarray, p: np.ndarray, m: np.ndarray, v: np.ndarray, alpha: floa
 
 
 def mean_gradients(grads: Sequence[Sequence[np.ndarray]], numel: Sequence[int], n_chunks: int, *, dtype="f32",
-                   align_bytes: int = 256, ring_rotate: int = 1) -> List[np.ndarray]:
+                   align_bytes: int = 256, ring_rotate: int = 1, scales=None) -> List[np.ndarray]:
     """S1..S4: pack, fold, scale, unpack -> the T averaged gradient tensors (float32)."""
     K = len(grads)
     geo = Geometry(numel, n_chunks, align_bytes, dtype)
     packed = [pack(geo, grads[k]) for k in range(K)]
-    return unpack(geo, scale(direct_fold(geo, packed, ring_rotate), K))
+    return unpack(geo, scale(direct_fold(geo, packed, ring_rotate, scales), K))
 
 
 def allreduce_step(grads: Sequence[Sequence[np.ndarray]], params: List[np.ndarray], vels: List[np.ndarray],
                    n_chunks: int, lr: float, mu: float, wd: float, *, dtype="f32", align_bytes: int = 256,
-                   ring_rotate: int = 1) -> List[np.ndarray]:
+                   ring_rotate: int = 1, scales=None) -> List[np.ndarray]:
     """The whole iteration, step after step with every intermediate materialised:
     pack each of the K replicas, fold, scale, unpack, MomentumSGD per tensor.
     ``grads[k][t]``; params/vels are updated in place; returns the mean gradients."""
     K = len(grads)
     geo = Geometry([p.size for p in params], n_chunks, align_bytes, dtype)
     packed = [pack(geo, grads[k]) for k in range(K)]
-    total = direct_fold(geo, packed, ring_rotate)
+    total = direct_fold(geo, packed, ring_rotate, scales)
     gbar = scale(total, K)
     mean = unpack(geo, gbar)
     for t in range(geo.T):

@@ -22,8 +22,9 @@
  * binary16 decode against numpy.  No function here is "parity unpinned".
  *
  * dtype codes: 0 = float32 gradients, 1 = IEEE binary16 gradients, 2 = bfloat16
- * gradients (the upper 16 bits of a binary32).  16-bit types are storage only;
- * every sum is accumulated in float32.
+ * gradients (the upper 16 bits of a binary32), 3 = int8 gradients with one float32
+ * scale per (replica, ring chunk): value = (float)q * scale, the product rounded once.
+ * The narrow types are storage only; every sum is accumulated in float32.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -33,6 +34,7 @@
 #define ORC_F32 0
 #define ORC_F16 1
 #define ORC_BF16 2
+#define ORC_I8S 3
 
 /* ---- binary16 -> binary32, bit level (exact, incl. subnormals, Inf, NaN) ---- */
 float orc_half_bits_to_float(uint16_t h)
@@ -80,8 +82,12 @@ void orc_float_to_bf16_array(int64_t n, const float *in, uint16_t *out)
     for (int64_t i = 0; i < n; ++i) out[i] = orc_float_to_bf16_bits(in[i]);
 }
 
-static float load_grad(const void *base, int dtype, int64_t i)
+static float load_grad(const void *base, int dtype, int64_t i, float scale)
 {
+    if (dtype == ORC_I8S) {
+        float q = (float)((const int8_t *)base)[i];   /* exact */
+        return q * scale;
+    }
     if (dtype == ORC_F16)
         return orc_half_bits_to_float(((const uint16_t *)base)[i]);
     if (dtype == ORC_BF16)
@@ -89,7 +95,7 @@ static float load_grad(const void *base, int dtype, int64_t i)
     return ((const float *)base)[i];
 }
 
-static int elem_bytes(int dtype) { return dtype == ORC_F32 ? 4 : 2; }
+static int elem_bytes(int dtype) { return dtype == ORC_F32 ? 4 : dtype == ORC_I8S ? 1 : 2; }
 
 /* ---- geometry of the packed buffer ------------------------------------------
  * off[0] = 0, off[t+1] = off[t] + numel[t], N = off[T].
@@ -137,16 +143,17 @@ void orc_pack(int T, const int64_t *numel, const void *const *tensors, int dtype
  * orc_ring_allreduce), s = 0 otherwise (plain rank order 0, 1, ..., K-1).
  * Chunks are independent, so the OpenMP loop over chunks changes no bit. */
 void orc_direct_fold(int K, int C, int64_t chunk_elems, const void *const *packed /* [K] */,
-                     int dtype, int ring_rotate, float *sum /* [C*chunk_elems] */)
+                     int dtype, int ring_rotate, const float *const *scales /* [K][C], int8 only, else NULL */,
+                     float *sum /* [C*chunk_elems] */)
 {
 #pragma omp parallel for schedule(static)
     for (int c = 0; c < C; ++c) {
         int s = ring_rotate ? c % K : 0;
         for (int64_t i = c * chunk_elems; i < (c + 1) * chunk_elems; ++i) {
-            float acc = load_grad(packed[s], dtype, i);
+            float acc = load_grad(packed[s], dtype, i, scales ? scales[s][c] : 1.0f);
             for (int j = 1; j < K; ++j) {
                 int r = (s + j) % K;
-                acc = acc + load_grad(packed[r], dtype, i);
+                acc = acc + load_grad(packed[r], dtype, i, scales ? scales[r][c] : 1.0f);
             }
             sum[i] = acc;
         }

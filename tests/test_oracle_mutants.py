@@ -43,6 +43,9 @@ MUTANTS = [
     ("bf16_encode_truncates", "if (rem > 0x8000u || (rem == 0x8000u && (kept & 1u))) ++kept;", "(void)rem;"),
     ("bf16_encode_ties_away", "(rem == 0x8000u && (kept & 1u))) ++kept;", "(rem == 0x8000u)) ++kept;"),
     ("bf16_nan_becomes_inf", "return (uint16_t)((x >> 16) | 0x0040u);", "return (uint16_t)(x >> 16);"),
+    ("int8_scale_of_wrong_chunk", "load_grad(packed[r], dtype, i, scales ? scales[r][c] : 1.0f)", "load_grad(packed[r], dtype, i, scales ? scales[r][0] : 1.0f)"),
+    ("int8_scale_of_wrong_replica", "load_grad(packed[r], dtype, i, scales ? scales[r][c] : 1.0f)", "load_grad(packed[r], dtype, i, scales ? scales[s][c] : 1.0f)"),
+    ("int8_read_as_unsigned", "float q = (float)((const int8_t *)base)[i];", "float q = (float)((const uint8_t *)base)[i];"),
     ("adam_first_moment_no_decay", "float mn = m[i] + t2;", "float mn = m[i] + t1;"),
     ("adam_second_moment_uses_g", "float t3 = gi * gi;", "float t3 = gi;"),
     ("adam_eps_inside_sqrt", "float s = sqrtf(vn);\n        float den = s + eps;", "float s = sqrtf(vn + eps);\n        float den = s;"),

@@ -492,3 +492,46 @@ def test_bf16_storage_fold_equals_fold_of_decoded_values():
     assert gb.chunk_elems == g32.chunk_elems == ce
     dec = [(x.astype(np.uint32) << 16).view(np.float32) for x in b]
     assert np.array_equal(oracle.direct_fold(gb, b).view(np.uint32), oracle.direct_fold(g32, dec).view(np.uint32))
+
+
+# ------------------------------------------------------------------ int8 with per-chunk scales
+def test_int8_unit_scale_sums_are_exact_integers():
+    rng = np.random.default_rng(41)
+    K, C, ce = 5, 3, 256
+    geo = oracle.Geometry([C * ce], C, 256, "i8s")
+    assert geo.chunk_elems == ce and geo.L == C * ce
+    q = [rng.integers(-127, 128, C * ce).astype(np.int8) for _ in range(K)]
+    ones = [np.ones(C, np.float32)] * K
+    got = oracle.direct_fold(geo, q, 1, ones)
+    assert np.array_equal(got, np.sum(np.stack(q).astype(np.int64), axis=0).astype(np.float32))
+
+
+def test_int8_scale_belongs_to_replica_and_chunk():
+    # replica k, chunk c carries scale 2^(k + 4c): every product and sum is exact, so the result
+    # reveals exactly which scale met which element
+    K, C, ce = 3, 4, 256
+    geo = oracle.Geometry([C * ce], C, 256, "i8s")
+    rng = np.random.default_rng(42)
+    q = [rng.integers(-100, 101, C * ce).astype(np.int8) for _ in range(K)]
+    scales = [np.array([2.0 ** (k + 4 * c) for c in range(C)], np.float32) for k in range(K)]
+    got = oracle.direct_fold(geo, q, 1, scales)
+    want = np.zeros(C * ce, np.float64)
+    for k in range(K):
+        for c in range(C):
+            want[c * ce:(c + 1) * ce] += q[k][c * ce:(c + 1) * ce].astype(np.float64) * 2.0 ** (k + 4 * c)
+    assert np.array_equal(got.astype(np.float64), want)
+
+
+def test_int8_fold_equals_fold_of_decoded_float32():
+    rng = np.random.default_rng(43)
+    K, C, ce = 4, 4, 256
+    geo8 = oracle.Geometry([C * ce], C, 256, "i8s")
+    geo32 = oracle.Geometry([C * ce], C, 1024, "f32")        # same chunk length in elements
+    assert geo32.chunk_elems == ce
+    q = [rng.integers(-127, 128, C * ce).astype(np.int8) for _ in range(K)]
+    scales = [(rng.random(C) * 1e-4 + 1e-6).astype(np.float32) for _ in range(K)]
+    dec = [(q[k].astype(np.float32).reshape(C, ce) * scales[k][:, None]).reshape(-1) for k in range(K)]   # one rounding
+    for rot in (0, 1):
+        a = oracle.direct_fold(geo8, q, rot, scales)
+        b = oracle.direct_fold(geo32, dec, rot)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
