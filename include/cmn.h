@@ -60,7 +60,10 @@ enum cmn_status {
 enum cmn_dtype {
     CMN_F32 = 0, /* gradients stored as IEEE binary32 */
     CMN_F16 = 1, /* gradients stored as IEEE binary16, decoded exactly and summed in binary32 */
-    CMN_BF16 = 2 /* gradients stored as bfloat16 (upper half of a binary32), same treatment   */
+    CMN_BF16 = 2, /* gradients stored as bfloat16 (upper half of a binary32), same treatment  */
+    CMN_I8S = 3   /* gradients stored as int8 with one float32 scale per (replica, ring chunk):
+                     value = (float)q * scale, the product rounded once, summed in binary32;
+                     scales are bound with cmn_plan_bind_scales                               */
 };
 
 /* Where a fused step puts the averaged gradient. */
@@ -93,7 +96,7 @@ typedef struct cmn_tile {
     int32_t len;
     int32_t tensor;
     int32_t start_rank;
-    int32_t reserved;
+    int32_t chunk;          /* index of that ring chunk (selects the scale of int8 gradients) */
     int8_t head[8];
 } cmn_tile;
 
@@ -183,6 +186,15 @@ int cmn_allreduce_step_range(const cmn_plan *plan, int tensor_begin, int tensor_
  * first moment lives in the tensors bound as vel_ptrs.  Call after cmn_plan_bind (which must
  * have bound parameters); re-uploads the plan's tables and waits for `stream`. */
 int cmn_plan_bind_adam(cmn_plan *plan, void *const *second_moment_ptrs /* host [T] */, void *stream);
+
+/* Bind the scales of CMN_I8S gradients: host array of K device pointers, scale_ptrs[k] ->
+ * n_chunks float32 values, element c scaling every element of replica k whose packed index
+ * lies in ring chunk c.  The scale arrays are read by every later launch (they may be
+ * rewritten between launches).  Call after cmn_plan_bind; re-uploads the tables and waits
+ * for `stream`.  cmn_ring_reduce and the fused steps return CMN_EUNBOUND for a CMN_I8S plan
+ * without scales, and CMN_EINVAL for CMN_MEAN_TO_ALL_REPLICAS (re-quantising the average is
+ * not defined).  Errors: CMN_ENULL, CMN_EALIGN, CMN_EINVAL (plan is not CMN_I8S). */
+int cmn_plan_bind_scales(cmn_plan *plan, const float *const *scale_ptrs /* host [K] */, void *stream);
 
 /* Fused step with Adam in place of MomentumSGD (the optimizer the paper's Listing 1 wraps;
  * Section 3.3: the multi-node optimizer behaves like the optimizer it wraps).  Per element,

@@ -18,8 +18,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcmn.so")
 
 CMN_OK, CMN_EINVAL, CMN_ENULL, CMN_ESIZE, CMN_EALIGN, CMN_EUNBOUND, CMN_EHIP, CMN_ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
-CMN_F32, CMN_F16, CMN_BF16 = 0, 1, 2
-_DT = {"f32": CMN_F32, "f16": CMN_F16, "bf16": CMN_BF16, CMN_F32: CMN_F32, CMN_F16: CMN_F16, CMN_BF16: CMN_BF16}
+CMN_F32, CMN_F16, CMN_BF16, CMN_I8S = 0, 1, 2, 3
+_DT = {"f32": CMN_F32, "f16": CMN_F16, "bf16": CMN_BF16, "i8s": CMN_I8S,
+       CMN_F32: CMN_F32, CMN_F16: CMN_F16, CMN_BF16: CMN_BF16, CMN_I8S: CMN_I8S}
 
 
 CMN_MEAN_NONE, CMN_MEAN_TO_MEAN_GRADS, CMN_MEAN_TO_ALL_REPLICAS = 0, 1, 2
@@ -29,11 +30,11 @@ CMN_MEAN_NONE, CMN_MEAN_TO_MEAN_GRADS, CMN_MEAN_TO_ALL_REPLICAS = 0, 1, 2
 
 class cmn_tile(ctypes.Structure):
     _fields_ = [("e0", ctypes.c_int64), ("len", ctypes.c_int32), ("tensor", ctypes.c_int32),
-                ("start_rank", ctypes.c_int32), ("reserved", ctypes.c_int32), ("head", ctypes.c_int8 * 8)]
+                ("start_rank", ctypes.c_int32), ("chunk", ctypes.c_int32), ("head", ctypes.c_int8 * 8)]
 
 
 TILE_DTYPE = np.dtype([("e0", "<i8"), ("len", "<i4"), ("tensor", "<i4"), ("start_rank", "<i4"),
-                       ("reserved", "<i4"), ("head", "i1", (8,))])
+                       ("chunk", "<i4"), ("head", "i1", (8,))])
 
 
 class CmnError(RuntimeError):
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
     L.cmn_plan_workspace_bytes.argtypes = [vp]
     L.cmn_plan_describe_tiles.restype = ctypes.c_int
     L.cmn_plan_describe_tiles.argtypes = [vp, vpp, vpp, vpp, vpp, vpp, ctypes.POINTER(cmn_tile)]
+    L.cmn_plan_bind_scales.restype = ctypes.c_int
+    L.cmn_plan_bind_scales.argtypes = [vp, vpp, vp]
     L.cmn_plan_bind_adam.restype = ctypes.c_int
     L.cmn_plan_bind_adam.argtypes = [vp, vpp, vp]
     L.cmn_plan_bind.restype = ctypes.c_int
@@ -173,6 +176,10 @@ def cmn_plan_describe_tiles(h, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, 
                                        _ptr_array(mean_grad_ptrs), _ptr_array(second_moment_ptrs),
                                        out.ctypes.data_as(ctypes.POINTER(cmn_tile)) if n else None)
     return rc, out
+
+
+def cmn_plan_bind_scales(h, scale_ptrs, stream=None) -> int:
+    return lib().cmn_plan_bind_scales(h, _ptr_array(scale_ptrs), _stream(stream))
 
 
 def cmn_plan_bind_adam(h, second_moment_ptrs, stream=None) -> int:
@@ -288,6 +295,11 @@ class Plan:
     def allreduce_step_range(self, tensor_begin, tensor_end, lr, mu, wd, mean_dest=CMN_MEAN_NONE, stream=None) -> None:
         _check(cmn_allreduce_step_range(self.h, tensor_begin, tensor_end, lr, mu, wd, mean_dest, stream),
                "cmn_allreduce_step_range")
+
+    def bind_scales(self, scales, stream=None) -> None:
+        """scales[k]: CUDA float32 tensor of n_chunks scales of replica k (int8 gradient storage)."""
+        _check(cmn_plan_bind_scales(self.h, scales, stream), "cmn_plan_bind_scales")
+        self._keep = (self._keep, scales)
 
     def bind_adam(self, second_moments, stream=None) -> None:
         _check(cmn_plan_bind_adam(self.h, second_moments, stream), "cmn_plan_bind_adam")

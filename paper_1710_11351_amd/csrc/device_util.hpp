@@ -18,6 +18,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef signed char i8x16 __attribute__((ext_vector_type(16)));
 
 // Storage traits of the gradient element type.
 template <int DT> struct GradT;
@@ -26,10 +27,10 @@ template <> struct GradT<CMN_F32> {
     using elem = float;
     using raw = f32x4;                 // one 16-byte load
     static constexpr int VEC = 4;      // elements per 16-byte vector
-    static __device__ __forceinline__ void accumulate(float (&acc)[4], const raw &r) {
+    static __device__ __forceinline__ void accumulate(float (&acc)[4], const raw &r, float /*scale*/) {
         acc[0] = acc[0] + r.x; acc[1] = acc[1] + r.y; acc[2] = acc[2] + r.z; acc[3] = acc[3] + r.w;
     }
-    static __device__ __forceinline__ float decode(elem x) { return x; }
+    static __device__ __forceinline__ float decode(elem x, float /*scale*/) { return x; }
     static __device__ __forceinline__ elem encode(float x) { return x; }
     static __device__ __forceinline__ raw encode_vec(const float (&g)[4]) { return raw{g[0], g[1], g[2], g[3]}; }
 };
@@ -38,11 +39,11 @@ template <> struct GradT<CMN_F16> {
     using elem = _Float16;
     using raw = f16x8;
     static constexpr int VEC = 8;
-    static __device__ __forceinline__ void accumulate(float (&acc)[8], const raw &r) {
+    static __device__ __forceinline__ void accumulate(float (&acc)[8], const raw &r, float /*scale*/) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = acc[i] + static_cast<float>(r[i]);  // exact widening
     }
-    static __device__ __forceinline__ float decode(elem x) { return static_cast<float>(x); }
+    static __device__ __forceinline__ float decode(elem x, float /*scale*/) { return static_cast<float>(x); }
     static __device__ __forceinline__ elem encode(float x) { return static_cast<elem>(x); }  // nearest even
     static __device__ __forceinline__ raw encode_vec(const float (&g)[8]) {
         raw r;
@@ -56,7 +57,7 @@ template <> struct GradT<CMN_BF16> {
     using elem = unsigned short;        // raw bfloat16 bit pattern
     using raw = u16x8;
     static constexpr int VEC = 8;
-    static __device__ __forceinline__ float decode(elem x) {
+    static __device__ __forceinline__ float decode(elem x, float /*scale*/ = 1.0f) {
         return __builtin_bit_cast(float, static_cast<unsigned>(x) << 16);   // exact
     }
     static __device__ __forceinline__ elem encode(float x) {                 // nearest, ties to even
@@ -64,7 +65,7 @@ template <> struct GradT<CMN_BF16> {
         if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<elem>((u >> 16) | 0x40u);   // NaN stays NaN
         return static_cast<elem>((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
     }
-    static __device__ __forceinline__ void accumulate(float (&acc)[8], const raw &r) {
+    static __device__ __forceinline__ void accumulate(float (&acc)[8], const raw &r, float /*scale*/) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = acc[i] + decode(r[i]);
     }
@@ -74,6 +75,23 @@ template <> struct GradT<CMN_BF16> {
         for (int i = 0; i < 8; ++i) r[i] = encode(g[i]);
         return r;
     }
+};
+
+template <> struct GradT<CMN_I8S> {
+    using elem = signed char;
+    using raw = i8x16;
+    static constexpr int VEC = 16;
+    static __device__ __forceinline__ float decode(elem q, float scale) {
+        const float f = static_cast<float>(q);   // exact
+        return f * scale;                        // rounded once
+    }
+    static __device__ __forceinline__ void accumulate(float (&acc)[16], const raw &r, float scale) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = acc[i] + decode(r[i], scale);
+    }
+    // the average is never written back in this format
+    static __device__ __forceinline__ elem encode(float) { return 0; }
+    static __device__ __forceinline__ raw encode_vec(const float (&)[16]) { return raw{}; }
 };
 
 template <typename V>
@@ -110,6 +128,9 @@ __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned
 __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, u16x8 v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
 }
+__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, i8x16 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
+}
 
 // The K-term sum starts from -0.0f because x + (-0.0f) == x for every x, signed
 // zeros included, so the first addition reproduces the first gradient exactly.
@@ -122,27 +143,32 @@ __device__ __forceinline__ int ring_rank(int s, int j, int K) {
 }
 
 // Fold replicas [j, j + B) of the fixed order into acc: B vector loads are issued back to
-// back, then added strictly in order.  ptr_of(j) yields the address of replica j's vector.
-template <int DT, int B, typename PtrFn>
-__device__ __forceinline__ void fold_batch(float (&acc)[GradT<DT>::VEC], int j, PtrFn ptr_of) {
+// back, then added strictly in order.  ptr_of(j) yields the address of replica j's vector,
+// scale_of(j) its scale (only int8 storage uses it).
+template <int DT, int B, typename PtrFn, typename ScaleFn>
+__device__ __forceinline__ void fold_batch(float (&acc)[GradT<DT>::VEC], int j, PtrFn ptr_of, ScaleFn scale_of) {
     using G = GradT<DT>;
     typename G::raw g[B];
+    float sc[B];
 #pragma unroll
-    for (int u = 0; u < B; ++u) g[u] = load_stream<typename G::raw>(ptr_of(j + u));
+    for (int u = 0; u < B; ++u) {
+        g[u] = load_stream<typename G::raw>(ptr_of(j + u));
+        sc[u] = DT == CMN_I8S ? scale_of(j + u) : 1.0f;
+    }
 #pragma unroll
-    for (int u = 0; u < B; ++u) G::accumulate(acc, g[u]);
+    for (int u = 0; u < B; ++u) G::accumulate(acc, g[u], sc[u]);
 }
 
 // The whole K-term fold: batches of U, then the remainder in halving batches so that a K
 // that is not a multiple of U still keeps several loads in flight.
-template <int DT, int U, typename PtrFn>
-__device__ __forceinline__ void fold_all(float (&acc)[GradT<DT>::VEC], int K, PtrFn ptr_of) {
+template <int DT, int U, typename PtrFn, typename ScaleFn>
+__device__ __forceinline__ void fold_all(float (&acc)[GradT<DT>::VEC], int K, PtrFn ptr_of, ScaleFn scale_of) {
     int j = 0;
-    for (; j + U <= K; j += U) fold_batch<DT, U>(acc, j, ptr_of);
-    if (U > 8 && j + 8 <= K) { fold_batch<DT, 8>(acc, j, ptr_of); j += 8; }
-    if (U > 4 && j + 4 <= K) { fold_batch<DT, 4>(acc, j, ptr_of); j += 4; }
-    if (U > 2 && j + 2 <= K) { fold_batch<DT, 2>(acc, j, ptr_of); j += 2; }
-    if (j < K) fold_batch<DT, 1>(acc, j, ptr_of);
+    for (; j + U <= K; j += U) fold_batch<DT, U>(acc, j, ptr_of, scale_of);
+    if (U > 8 && j + 8 <= K) { fold_batch<DT, 8>(acc, j, ptr_of, scale_of); j += 8; }
+    if (U > 4 && j + 4 <= K) { fold_batch<DT, 4>(acc, j, ptr_of, scale_of); j += 4; }
+    if (U > 2 && j + 2 <= K) { fold_batch<DT, 2>(acc, j, ptr_of, scale_of); j += 2; }
+    if (j < K) fold_batch<DT, 1>(acc, j, ptr_of, scale_of);
 }
 
 // Optimizer hyper-parameters as the kernels receive them (by value).

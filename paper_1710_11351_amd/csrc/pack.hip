@@ -146,6 +146,7 @@ extern "C" int cmn_pack(const cmn_plan *plan, void *packed, void *stream) {
 #define CMN_LAUNCH_PACK(DT, LDS) \
     hipLaunchKernelGGL((k_pack<DT, LDS>), grid, dim3(kBlock), shm, s, off, rows, packed, T, N, L)
     if (plan->dtype == CMN_F32) { if (lds) CMN_LAUNCH_PACK(CMN_F32, true); else CMN_LAUNCH_PACK(CMN_F32, false); }
+    else if (plan->dtype == CMN_I8S) { if (lds) CMN_LAUNCH_PACK(CMN_I8S, true); else CMN_LAUNCH_PACK(CMN_I8S, false); }
     else /* any 16-bit type: a bit copy */ { if (lds) CMN_LAUNCH_PACK(CMN_F16, true); else CMN_LAUNCH_PACK(CMN_F16, false); }
 #undef CMN_LAUNCH_PACK
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;

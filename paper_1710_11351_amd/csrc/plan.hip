@@ -23,6 +23,7 @@ static WorkspaceLayout make_layout(int T, int K, int64_t n_tiles) {
     w.vel_ptrs = o;   o = round256(o + sizeof(void *) * size_t(T));
     w.mean_ptrs = o;  o = round256(o + sizeof(void *) * size_t(T));
     w.state2_ptrs = o; o = round256(o + sizeof(void *) * size_t(T));
+    w.scale_ptrs = o;  o = round256(o + sizeof(void *) * size_t(K));
     w.tiles = o;      o = round256(o + sizeof(cmn_tile) * size_t(n_tiles));
     w.total = o < 256 ? 256 : o;
     return w;
@@ -43,7 +44,7 @@ static int64_t for_each_tile(const cmn_plan &p, F &&emit) {
             if (end > n) end = n;
             const int64_t tile_end = (e / p.tile_elems + 1) * p.tile_elems;
             if (end > tile_end) end = tile_end;
-            emit(t, e, int32_t(end - e), p.ring_rotate ? int32_t(c % p.K) : 0);
+            emit(t, e, int32_t(end - e), p.ring_rotate ? int32_t(c % p.K) : 0, int32_t(c));
             ++count;
             e = end;
         }
@@ -108,9 +109,9 @@ void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *p
         }
     }
     int64_t i = 0;
-    for_each_tile(p, [&](int t, int64_t e0, int32_t len, int32_t start) {
+    for_each_tile(p, [&](int t, int64_t e0, int32_t len, int32_t start, int32_t chunk) {
         cmn_tile &tl = out[i++];
-        tl.e0 = e0; tl.len = len; tl.tensor = t; tl.start_rank = start; tl.reserved = 0;
+        tl.e0 = e0; tl.len = len; tl.tensor = t; tl.start_rank = start; tl.chunk = chunk;
         for (int v = 0; v < 8; ++v) {
             const int a = h[size_t(t) * 8 + v];
             const int w = (v == CMN_HEAD_SGD || v == CMN_HEAD_ADAM_OPT) ? 4 : vec;
@@ -137,7 +138,7 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
     *out = nullptr;
     if (n_tensors < 0 || K < 1 || n_chunks < 1) return CMN_EINVAL;
     if (n_tensors > 0 && !numel) return CMN_ENULL;
-    if (grad_dtype != CMN_F32 && grad_dtype != CMN_F16 && grad_dtype != CMN_BF16) return CMN_EINVAL;
+    if (grad_dtype < CMN_F32 || grad_dtype > CMN_I8S) return CMN_EINVAL;
     if (ring_rotate != 0 && ring_rotate != 1) return CMN_EINVAL;
     if (align_bytes < 16 || (align_bytes & (align_bytes - 1)) != 0) return CMN_EINVAL;
     if (n_tensors > kMaxTensors || K > kMaxReplicas || align_bytes > (1 << 20)) return CMN_ESIZE;
@@ -175,7 +176,7 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
     } catch (...) { delete p; return CMN_ENOMEM; }
     {
         std::vector<int64_t> &ft = p->first_tile;
-        p->n_tiles = for_each_tile(*p, [&ft](int t, int64_t, int32_t, int32_t) { ++ft[size_t(t) + 1]; });
+        p->n_tiles = for_each_tile(*p, [&ft](int t, int64_t, int32_t, int32_t, int32_t) { ++ft[size_t(t) + 1]; });
         for (int t = 0; t < n_tensors; ++t) ft[size_t(t) + 1] += ft[size_t(t)];
     }
     if (p->n_tiles > (int64_t(1) << 31) - 1) { delete p; return CMN_ESIZE; }
@@ -277,6 +278,7 @@ int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_p
     p->have_opt = param_ptrs != nullptr;
     p->have_mean = mean_grad_ptrs != nullptr;
     p->have_state2 = false;
+    p->have_scales = false;
     if (int rc2 = upload_image(p, dev_workspace, static_cast<hipStream_t>(stream))) return rc2;
     p->dev_ws = static_cast<char *>(dev_workspace);
     p->bound = true;
@@ -289,6 +291,22 @@ int cmn_plan_bind_adam(cmn_plan *plan, void *const *second_moment_ptrs, void *st
     if (int rc = check_ptr_array(plan, second_moment_ptrs, 1, 4)) return rc;
     std::memcpy(plan->staging.data() + plan->ws.state2_ptrs, second_moment_ptrs, sizeof(void *) * size_t(plan->T));
     plan->have_state2 = true;
+    plan->bound = false;
+    if (int rc = upload_image(plan, plan->dev_ws, static_cast<hipStream_t>(stream))) return rc;
+    plan->bound = true;
+    return CMN_OK;
+}
+
+int cmn_plan_bind_scales(cmn_plan *plan, const float *const *scale_ptrs, void *stream) {
+    if (!plan || !scale_ptrs) return CMN_ENULL;
+    if (plan->dtype != CMN_I8S) return CMN_EINVAL;
+    if (!plan->bound) return CMN_EUNBOUND;
+    for (int k = 0; k < plan->K; ++k) {
+        if (!scale_ptrs[k]) return CMN_ENULL;
+        if (reinterpret_cast<uintptr_t>(scale_ptrs[k]) % 4) return CMN_EALIGN;
+    }
+    std::memcpy(plan->staging.data() + plan->ws.scale_ptrs, scale_ptrs, sizeof(void *) * size_t(plan->K));
+    plan->have_scales = true;
     plan->bound = false;
     if (int rc = upload_image(plan, plan->dev_ws, static_cast<hipStream_t>(stream))) return rc;
     plan->bound = true;

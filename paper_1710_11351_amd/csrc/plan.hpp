@@ -17,7 +17,7 @@ constexpr int kBlock = 256;  // threads per workgroup of every kernel (4 wavefro
 // Elements of one cmn_tile at most: kBlock threads x one 16-byte vector x kTileIters.
 constexpr int kTileIters = 1;
 
-inline int elem_bytes(int dtype) { return dtype == CMN_F32 ? 4 : 2; }
+inline int elem_bytes(int dtype) { return dtype == CMN_F32 ? 4 : dtype == CMN_I8S ? 1 : 2; }
 inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }
 
 // Byte offsets of the tables inside the caller's device workspace (each 256-aligned).
@@ -29,6 +29,7 @@ struct WorkspaceLayout {
     size_t vel_ptrs = 0;     // float* [T]
     size_t mean_ptrs = 0;    // float* [T]
     size_t state2_ptrs = 0;  // float* [T]   Adam second moments
+    size_t scale_ptrs = 0;   // float* [K]   per-replica arrays of n_chunks scales (int8 gradients)
     size_t tiles = 0;        // cmn_tile [n_tiles]
     size_t total = 0;
 };
@@ -45,7 +46,7 @@ struct cmn_plan {
     cmn::WorkspaceLayout ws;
 
     // state set by cmn_plan_bind
-    bool bound = false, have_grads = false, have_opt = false, have_mean = false, have_state2 = false;
+    bool bound = false, have_grads = false, have_opt = false, have_mean = false, have_state2 = false, have_scales = false;
     char *dev_ws = nullptr;
     std::vector<unsigned char> staging;  // host image of the workspace
 };

@@ -15,12 +15,12 @@ constexpr int kReduceIters = 1;  // 16-byte vectors per thread per stream
 
 template <int DT, int U>
 __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__ packed,
-                                                        float *__restrict__ reduced, long long L,
+                                                        float *__restrict__ reduced,
+                                                        const float *const *__restrict__ scale_ptrs, long long L,
                                                         long long chunk_elems, int tiles_per_chunk, int K,
                                                         int ring_rotate) {
     using G = GradT<DT>;
     using elem = typename G::elem;
-    using raw = typename G::raw;
     constexpr int VEC = G::VEC;
     constexpr int TILE = kBlock * VEC * kReduceIters;
 
@@ -38,7 +38,9 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
-        fold_all<DT, U>(acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; });
+        fold_all<DT, U>(
+            acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
+            [&](int j) { return scale_ptrs[ring_rank(s, j, K)][c]; });
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
             f32x4 o;
@@ -64,11 +66,17 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
     const dim3 grid(unsigned(tpc * plan->C));
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CMN_LAUNCH_REDUCE(DT)                                                                              \
-    hipLaunchKernelGGL((k_ring_reduce<DT, 16>), grid, dim3(kBlock), 0, s, packed, reduced, (long long)plan->L, \
+    hipLaunchKernelGGL((k_ring_reduce<DT, 16>), grid, dim3(kBlock), 0, s, packed, reduced, scales, (long long)plan->L, \
                        (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate)
+    const float *const *scales = nullptr;
+    if (plan->dtype == CMN_I8S) {
+        if (!plan->bound || !plan->have_scales) return CMN_EUNBOUND;
+        scales = ws_ptr<const float *const>(plan, plan->ws.scale_ptrs);
+    }
     if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE(CMN_F32);
     else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE(CMN_F16);
-    else CMN_LAUNCH_REDUCE(CMN_BF16);
+    else if (plan->dtype == CMN_BF16) CMN_LAUNCH_REDUCE(CMN_BF16);
+    else CMN_LAUNCH_REDUCE(CMN_I8S);
 #undef CMN_LAUNCH_REDUCE
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }

@@ -29,7 +29,8 @@ template <int DT, int U, int SRC, int MEAN, int OPT>
 __global__ __launch_bounds__(kBlock) void k_step(
     const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
     float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
-    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs, int K, float inv_k, OptArgs o) {
+    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
+    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
     using G = GradT<DT>;
     using elem = typename G::elem;
     using raw = typename G::raw;
@@ -65,9 +66,9 @@ __global__ __launch_bounds__(kBlock) void k_step(
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
-            fold_all<DT, U>(gb, K, [&](int j) {
-                return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e;
-            });
+            fold_all<DT, U>(
+                gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e; },
+                [&](int j) { return scale_ptrs[ring_rank(s, j, K)][tl.chunk]; });
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
         }
@@ -114,8 +115,11 @@ __global__ __launch_bounds__(kBlock) void k_step(
             gb = m[e];
         } else {
             float acc = sum_identity();
-            for (int j = 0; j < K; ++j)
-                acc = acc + G::decode(static_cast<const elem *>(gcol[ring_rank(s, j, K)])[tl.e0 + e]);
+            for (int j = 0; j < K; ++j) {
+                const int r = ring_rank(s, j, K);
+                acc = acc + G::decode(static_cast<const elem *>(gcol[r])[tl.e0 + e],
+                                      DT == CMN_I8S ? scale_ptrs[r][tl.chunk] : 1.0f);
+            }
             gb = acc * inv_k;
         }
         float pi = p[e], a = s1[e], b = ADAM ? s2[e] : 0.0f;
@@ -138,7 +142,8 @@ inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_co
                        ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
                        ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<float *const>(p, p->ws.param_ptrs),
                        ws_ptr<float *const>(p, p->ws.vel_ptrs), ws_ptr<float *const>(p, p->ws.state2_ptrs),
-                       ws_ptr<float *const>(p, p->ws.mean_ptrs), p->K, 1.0f / float(p->K), o);
+                       ws_ptr<float *const>(p, p->ws.mean_ptrs), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
+                       p->K, 1.0f / float(p->K), o);
 }
 
 // Fused step (SRC_FOLD) over tensors [t0, t1): validation shared by the SGD and Adam entry points.
@@ -151,6 +156,10 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     if (!plan->have_grads || !plan->have_opt || (mean_dest == CMN_MEAN_TO_MEAN_GRADS && !plan->have_mean))
         return CMN_EUNBOUND;
     if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
+    if (plan->dtype == CMN_I8S) {
+        if (mean_dest == CMN_MEAN_TO_ALL_REPLICAS) return CMN_EINVAL;
+        if (!plan->have_scales) return CMN_EUNBOUND;
+    }
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -163,7 +172,9 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     } while (0)
     if (plan->dtype == CMN_F32) CMN_STEP_DTYPE(CMN_F32);
     else if (plan->dtype == CMN_F16) CMN_STEP_DTYPE(CMN_F16);
-    else CMN_STEP_DTYPE(CMN_BF16);
+    else if (plan->dtype == CMN_BF16) CMN_STEP_DTYPE(CMN_BF16);
+    else if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(CMN_I8S, CMN_MEAN_NONE);
+    else CMN_STEP_CASE(CMN_I8S, CMN_MEAN_TO_MEAN_GRADS);
 #undef CMN_STEP_DTYPE
 #undef CMN_STEP_CASE
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;

@@ -100,7 +100,8 @@ class Config:
     tensors: Tuple[TensorSpec, ...]
     K: int            # worker replicas
     n_chunks: int     # ring chunks
-    grad_dtype: str   # "f32" | "f16" | "bf16"  (storage type of gradients; bf16 as uint16 bit patterns)
+    grad_dtype: str   # "f32" | "f16" | "bf16" | "i8s"  (storage type; bf16 as uint16 bit patterns; "i8s" =
+                      # int8 + per-chunk scales, produced from the f32 draws by quantise_i8)
     grad_std: float
     per_layer_fan_in_scale: bool
     outlier_frac: float
@@ -187,7 +188,23 @@ def gen_grads(c: Config, step: int, k: int) -> List[np.ndarray]:
         return _split(flat.astype(np.float16), numel)  # round-to-nearest-even
     if c.grad_dtype == "bf16":
         return _split(_bf16_bits(flat), numel)         # uint16 bit patterns
-    return _split(flat, numel)
+    return _split(flat, numel)                         # "f32", and "i8s" before quantise_i8
+
+
+def quantise_i8(tensors: Sequence[np.ndarray], chunk_elems: int, n_chunks: int):
+    """Producer-side quantisation of one replica's float32 gradients for the int8 storage format:
+    per ring chunk (chunk_elems consecutive elements of the tight concatenation) one float32 scale
+    = max|g| / 127 (1 if the chunk is all zero or padding) and q = rint(g / scale) in [-127, 127].
+    Returns (list of int8 tensors, float32 array of n_chunks scales)."""
+    flat = np.concatenate([np.asarray(t, np.float32).reshape(-1) for t in tensors]) if tensors else np.zeros(0, np.float32)
+    q = np.zeros(flat.size, np.int8)
+    scales = np.ones(n_chunks, np.float32)
+    for c in range(n_chunks):
+        seg = flat[c * chunk_elems:(c + 1) * chunk_elems]
+        if seg.size and np.abs(seg).max() > 0:
+            scales[c] = np.float32(np.abs(seg).max()) / np.float32(127.0)
+            q[c * chunk_elems:c * chunk_elems + seg.size] = np.clip(np.rint(seg / scales[c]), -127, 127).astype(np.int8)
+    return _split(q, [np.asarray(t).size for t in tensors]), scales
 
 
 def gen_grads_f32_unquantised(c: Config, step: int, k: int) -> List[np.ndarray]:

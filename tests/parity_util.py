@@ -11,7 +11,7 @@ from paper_1710_11351_amd import workloads as wl
 
 def bits(a):
     a = np.ascontiguousarray(a)
-    if a.dtype == np.uint16:
+    if a.dtype in (np.uint16, np.int8):
         return a
     return a.view(np.uint16 if a.dtype == np.float16 else np.uint32)
 
@@ -50,7 +50,7 @@ class DeviceCase:
     def __init__(self, c: wl.Config, ring_rotate=1, misalign=0, with_mean=True, adam=False):
         import torch
         self.c, self.torch = c, torch
-        tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[c.grad_dtype]
+        tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i8s": torch.int8}[c.grad_dtype]
         self.plan = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype, ring_rotate)
 
         def alloc(dtype):
@@ -64,6 +64,10 @@ class DeviceCase:
         self.p, self.v = alloc(torch.float32), alloc(torch.float32)
         self.m = alloc(torch.float32) if with_mean else None
         self.plan.bind(self.grads, self.p, self.v, self.m)
+        self.scales = None
+        if c.grad_dtype == "i8s":
+            self.scales = [torch.ones(c.n_chunks, dtype=torch.float32, device="cuda") for _ in range(c.K)]
+            self.plan.bind_scales(self.scales)
         self.s = None
         if adam:
             self.s = alloc(torch.float32)
@@ -82,6 +86,9 @@ class DeviceCase:
                 d.copy_(self.torch.from_numpy(h.view(np.int16)).view(self.torch.bfloat16))
             else:
                 d.copy_(self.torch.from_numpy(h))
+
+    def set_scales(self, k, s_host):
+        self.scales[k].copy_(self.torch.from_numpy(np.ascontiguousarray(s_host, dtype=np.float32)))
 
     def get(self, tensors):
         self.torch.cuda.synchronize()
@@ -120,20 +127,26 @@ def run_parity(c: wl.Config, steps=3, ring_rotate=1, misalign=0, staged=True, fu
     geo = oracle.Geometry(c.numel, c.n_chunks, c.align_bytes, c.grad_dtype)
     if staged:
         dc = cases["staged"]
-        tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[c.grad_dtype]
-        packed = torch.full((c.K * geo.L + 64,), 7.0, dtype=tg, device="cuda")[: c.K * geo.L]
+        tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i8s": torch.int8}[c.grad_dtype]
+        packed = torch.full((c.K * geo.L + 64,), 7, dtype=tg, device="cuda")[: c.K * geo.L]
         reduced = torch.full((geo.L + 64,), 7.0, dtype=torch.float32, device="cuda")[: geo.L]
         assert dc.plan.L == geo.L
 
     for step in range(steps):
         grads = gen_all_grads(c, step)
+        scales = None
+        if c.grad_dtype == "i8s":                      # producer-side quantisation of the f32 draws
+            qs = [wl.quantise_i8(g, geo.chunk_elems, geo.C) for g in grads]
+            grads, scales = [q for q, _ in qs], [s for _, s in qs]
         print(f"[parity] {c.name} step {step}: inputs ready", flush=True)
         for dc in cases.values():
             for k in range(c.K):
                 dc.set_grads(k, grads[k])
+                if scales is not None:
+                    dc.set_scales(k, scales[k])
         # ---- oracle, step by step with intermediates
         packed_o = [oracle.pack(geo, grads[k]) for k in range(c.K)]
-        total_o = oracle.direct_fold(geo, packed_o, ring_rotate)
+        total_o = oracle.direct_fold(geo, packed_o, ring_rotate, scales)
         mean_o = oracle.unpack(geo, oracle.scale(total_o, c.K))
         for t in range(geo.T):
             if adam:

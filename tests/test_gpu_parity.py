@@ -13,7 +13,7 @@ def test_config1_mlp_k2():
 
 
 @pytest.mark.parametrize("rot", [0, 1])
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8s"])
 def test_ragged_list_with_empty_tensors(dtype, rot):
     # odd sizes, empty tensors, tiles and vectors that straddle tensor and chunk edges, K not a power of two
     numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3]
@@ -22,7 +22,7 @@ def test_ragged_list_with_empty_tensors(dtype, rot):
     run_parity(c, steps=3, ring_rotate=rot)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8s"])
 @pytest.mark.parametrize("misalign", [1, 3])
 def test_unaligned_base_pointers(dtype, misalign):
     c = wl.custom_config([1000, 4096, 37, 8192 + 5], K=4, n_chunks=4, grad_dtype=dtype, cfg=92)
@@ -52,6 +52,45 @@ def test_many_replicas_f16_k40():
 def test_bf16_storage_adam_k33():
     c = wl.custom_config([20000, 1000, 24, 4096], K=33, n_chunks=11, grad_dtype="bf16", cfg=86)
     run_parity(c, steps=2, opt="adam")
+
+
+def test_int8_storage_adam_and_many_chunks():
+    c = wl.custom_config([70000, 333, 4096, 5], K=9, n_chunks=18, grad_dtype="i8s", cfg=81, wd=1e-3)
+    run_parity(c, steps=2, opt="adam")
+
+
+def test_int8_storage_error_bound_and_argument_checks():
+    """Quantising with scale = max|g|/127 per chunk moves an element by at most scale/2 (plus one fp32
+    rounding of q*scale), so the mean moves by at most mean_k(scale_k)/2 * (1 + 2^-22)."""
+    import torch
+    import oracle
+    from paper_1710_11351_amd import binding as B
+    from parity_util import DeviceCase, gen_all_grads
+    numel = [36864, 64, 147456, 1000]
+    c = wl.custom_config(numel, K=8, n_chunks=8, grad_dtype="i8s", cfg=80, grad_std=1e-3)
+    dc = DeviceCase(c)
+    geo = oracle.Geometry(numel, c.n_chunks, 256, "i8s")
+    assert B.cmn_allreduce_step(dc.plan.h, c.lr, c.mu, 0., B.CMN_MEAN_TO_ALL_REPLICAS) == B.CMN_EINVAL
+    g32 = gen_all_grads(c, 0)
+    qs = [wl.quantise_i8(g, geo.chunk_elems, geo.C) for g in g32]
+    for k, (q, s) in enumerate(qs):
+        dc.set_grads(k, q); dc.set_scales(k, s)
+    dc.set_state(wl.gen_params(c), wl.gen_velocity(c))
+    dc.plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=True)
+    got = np.concatenate(dc.get(dc.m)).astype(np.float64)
+    want = np.mean(np.stack([np.concatenate(g).astype(np.float64) for g in g32]), axis=0)
+    half_step = np.mean(np.stack([s for _, s in qs]).astype(np.float64), axis=0) / 2          # per chunk
+    bound = np.repeat(half_step, geo.chunk_elems)[:want.size] * (1 + 2.0 ** -22) + 1e-12
+    assert np.all(np.abs(got - want) <= bound)
+    assert np.max(np.abs(got - want)) > 0.05 * bound.max()      # the quantisation error is really there
+    # a CMN_I8S plan without scales refuses to run
+    p2 = B.Plan(numel, c.K, c.n_chunks, 256, "i8s")
+    p2.bind(dc.grads, dc.p, dc.v, dc.m)
+    assert B.cmn_allreduce_step(p2.h, c.lr, c.mu, 0., 0) == B.CMN_EUNBOUND
+    assert B.cmn_ring_reduce(p2.h, 256, 512) == B.CMN_EUNBOUND
+    assert B.cmn_plan_bind_scales(dc.plan.h, None) == B.CMN_ENULL
+    pf = B.Plan(numel, 2, 2)
+    assert B.cmn_plan_bind_scales(pf.h, [256, 512]) == B.CMN_EINVAL             # not an int8 plan
 
 
 def test_bf16_storage_within_8e3_of_unquantised_fp32():

@@ -38,6 +38,7 @@ def test_strerror_is_total():
     (dict(numel=[4], K=1, n_chunks=1, align_bytes=48), B.CMN_EINVAL),
     (dict(numel=[4], K=1, n_chunks=1, align_bytes=8), B.CMN_EINVAL),
     (dict(numel=[4], K=1, n_chunks=1, grad_dtype=7), B.CMN_EINVAL),
+    (dict(numel=[4], K=1, n_chunks=1, grad_dtype=-1), B.CMN_EINVAL),
     (dict(numel=[4], K=1, n_chunks=1, ring_rotate=2), B.CMN_EINVAL),
     (dict(numel=[4], K=5000, n_chunks=1), B.CMN_ESIZE),
     (dict(numel=[1 << 50], K=1, n_chunks=1), B.CMN_ESIZE),
@@ -96,7 +97,7 @@ def test_plan_geometry_agrees_with_oracle_on_random_lists():
         T = int(rng.integers(0, 12))
         numel = [int(x) for x in rng.choice([0, 1, 3, 63, 64, 65, 1000, 4097], T)]
         C = int(rng.integers(1, 9))
-        dt = ["f32", "f16"][int(rng.integers(0, 2))]
+        dt = ["f32", "f16", "bf16", "i8s"][int(rng.integers(0, 4))]
         align = int(rng.choice([16, 64, 256, 1024]))
         p = B.Plan(numel, int(rng.integers(1, 9)), C, align, dt)
         g = oracle.Geometry(numel, C, align, dt)
