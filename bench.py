@@ -33,7 +33,7 @@ def log(*a):
 
 def algorithmic_bytes(c, entry="step", mean_dest=0, opt="sgd"):
     """Bytes the method must move per launch (padding, tables, scratch not counted)."""
-    eg = 2 if c.grad_dtype == "f16" else 4
+    eg = {"f32": 4, "f16": 2, "bf16": 2, "i8s": 1}[c.grad_dtype]
     N, K = c.N, c.K
     state = 24 if opt == "adam" else 16                         # p + optimizer state, read and written
     mean = {0: 0, 1: 4, 2: K * eg}[mean_dest]                   # averaged gradient written once / K times
@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--staged", action="store_true", help="also time the four staged entry points")
     ap.add_argument("--mean-dest", type=int, default=0, choices=(0, 1, 2),
                     help="0: mean gradient not stored; 1: stored once; 2: written back to all K replicas")
+    ap.add_argument("--grad-dtype", default=None, choices=("f32", "f16", "bf16", "i8s"),
+                    help="override the gradient storage type of the workload (i8s: random int8 + scales)")
     ap.add_argument("--opt", default="sgd", choices=("sgd", "adam"), help="optimizer fused into the step")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
@@ -91,9 +93,13 @@ def main():
     B.lib()                                         # fail loudly if libcmn.so is missing
     torch.cuda.set_device(0)
     c = wl.config(args.config)
+    if args.grad_dtype and args.grad_dtype != c.grad_dtype:
+        import dataclasses
+        c = dataclasses.replace(c, grad_dtype=args.grad_dtype, name=f"{c.name}+{args.grad_dtype}")
+        args.no_cpu = True
     log(f"[bench] workload {c.name}: T={len(c.tensors)} N={c.N} K={c.K} chunks={c.n_chunks} grads={c.grad_dtype}")
 
-    tg = torch.float16 if c.grad_dtype == "f16" else torch.float32
+    tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i8s": torch.int8}[c.grad_dtype]
     t0 = time.time()
     host_grads = []                                 # kept for the CPU leg when it fits
     keep_host = not args.no_cpu
@@ -101,9 +107,18 @@ def main():
     from concurrent.futures import ThreadPoolExecutor
     with ThreadPoolExecutor(max_workers=8) as ex:   # numpy's generators release the GIL
         for k0 in range(0, c.K, 8):
-            batch = list(ex.map(lambda k: wl.gen_grads(c, 0, k), range(k0, min(c.K, k0 + 8))))
+            if c.grad_dtype == "i8s":               # timing only: random int8 payload, scales bound below
+                batch = [[torch.randint(-127, 128, (n,), dtype=torch.int8, device="cuda") for n in c.numel]
+                         for _ in range(k0, min(c.K, k0 + 8))]
+            else:
+                batch = list(ex.map(lambda k: wl.gen_grads(c, 0, k), range(k0, min(c.K, k0 + 8))))
             for g in batch:
-                d_g.append(B.upload_tensors(g))     # every tensor its own allocation
+                if c.grad_dtype == "i8s":
+                    d_g.append(g)
+                elif c.grad_dtype == "bf16":
+                    d_g.append([torch.from_numpy(h.view(np.int16)).view(torch.bfloat16).cuda() for h in g])
+                else:
+                    d_g.append(B.upload_tensors(g))     # every tensor its own allocation
                 if keep_host:
                     host_grads.append(g)
             log(f"[bench] generated + uploaded replicas {len(d_g)}/{c.K} ({time.time() - t0:.1f}s)")
@@ -112,6 +127,9 @@ def main():
     d_m = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in c.numel]
     plan = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype)
     plan.bind(d_g, d_p, d_v, d_m)
+    if c.grad_dtype == "i8s":
+        d_sc = [torch.rand(c.n_chunks, device="cuda") * 1e-5 + 1e-6 for _ in range(c.K)]
+        plan.bind_scales(d_sc)
     if args.opt == "adam":
         d_s = [torch.zeros(n, dtype=torch.float32, device="cuda") for n in c.numel]
         plan.bind_adam(d_s)
