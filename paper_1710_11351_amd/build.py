@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "-fno-fast-math", "-fno-gpu-flush-denormals-to-zero",
     "-fhip-fp32-correctly-rounded-divide-sqrt",  # Adam's sqrt and division round like the host's
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the two-phase step kernel parks averaged gradients in a register array indexed by a fully
+    # unrolled loop; without full unrolling the array would fall into scratch memory
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
 

@@ -121,6 +121,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *base, unsigned
 __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f32x4 v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
 }
+// The same store with the default (write-back) policy.
+__device__ __forceinline__ void store_back(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 0);
+}
+template <bool WT>
+__device__ __forceinline__ void store_out(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f32x4 v) {
+    if (WT) store_through(r, byte_off, v); else store_back(r, byte_off, v);
+}
 
 __device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f16x8 v) {
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);

@@ -279,6 +279,14 @@ int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_p
     p->have_mean = mean_grad_ptrs != nullptr;
     p->have_state2 = false;
     p->have_scales = false;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            p->n_cus = cus;
+        const char *k = std::getenv("CMN_STEP_KERNEL");   // tuning knob: "stream" selects the one-pass kernel
+        p->two_phase = !(k && std::strcmp(k, "stream") == 0);
+    }
     if (int rc2 = upload_image(p, dev_workspace, static_cast<hipStream_t>(stream))) return rc2;
     p->dev_ws = static_cast<char *>(dev_workspace);
     p->bound = true;

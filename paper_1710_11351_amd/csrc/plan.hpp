@@ -39,6 +39,8 @@ struct WorkspaceLayout {
 struct cmn_plan {
     int T = 0, K = 1, C = 1, align_bytes = 256, dtype = CMN_F32, ring_rotate = 1;
     int tile_elems = 0;
+    int n_cus = 256;         // compute units of the device the plan was bound on
+    bool two_phase = true;   // fused steps use the two-phase persistent kernel (CMN_STEP_KERNEL=stream: the one-pass one)
     std::vector<int64_t> numel;  // [T]
     std::vector<int64_t> off;    // [T+1]
     int64_t N = 0, chunk_elems = 0, L = 0, n_tiles = 0;

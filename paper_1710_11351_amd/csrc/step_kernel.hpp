@@ -24,55 +24,57 @@ __device__ __forceinline__ constexpr int head_index() {
                              : (MEAN == CMN_MEAN_TO_MEAN_GRADS ? CMN_HEAD_STEP_MEAN : CMN_HEAD_STEP);
 }
 
-// U = gradient vectors requested back to back before the first one is consumed.
-template <int DT, int U, int SRC, int MEAN, int OPT>
-__global__ __launch_bounds__(kBlock) void k_step(
-    const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
-    float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
-    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
-    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
+// Everything a kernel needs to know about one tile, derived from its table entry.
+template <int DT, int SRC, int MEAN, int OPT>
+struct TileView {
     using G = GradT<DT>;
     using elem = typename G::elem;
-    using raw = typename G::raw;
-    constexpr int VEC = SRC == SRC_MEAN ? 4 : G::VEC;
-    constexpr bool ADAM = OPT == OPT_ADAM;
-    constexpr bool USE_MEAN_TENSOR = SRC == SRC_MEAN || MEAN == CMN_MEAN_TO_MEAN_GRADS;
+    static constexpr int VEC = SRC == SRC_MEAN ? 4 : G::VEC;
+    static constexpr bool ADAM = OPT == OPT_ADAM;
+    static constexpr bool USE_MEAN_TENSOR = SRC == SRC_MEAN || MEAN == CMN_MEAN_TO_MEAN_GRADS;
 
-    const cmn_tile tl = tiles[blockIdx.x];
-    const int t = tl.tensor, s = tl.start_rank, len = tl.len;
-    const void *const *gcol = grad_cols + size_t(t) * size_t(K);
-    float *p = param_ptrs[t] + tl.e0;
-    float *s1 = s1_ptrs[t] + tl.e0;
-    float *s2 = ADAM ? s2_ptrs[t] + tl.e0 : nullptr;
-    float *m = USE_MEAN_TENSOR ? mean_ptrs[t] + tl.e0 : nullptr;
+    long long e0;
+    int len, s, chunk, head, nvec, tail0;
+    const void *const *gcol;
+    float *p, *s1, *s2, *m;
 
-    int head = tl.head[head_index<SRC, MEAN, OPT>()];
-    if (head < 0 || head > len) head = len;
-    const int nvec = (len - head) / VEC;
-    const int tail0 = head + nvec * VEC;
-    const unsigned bytes = unsigned(len) * 4u;
-    const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, bytes);
-    const __amdgpu_buffer_rsrc_t s1_out = make_rsrc(s1, bytes);
-    const __amdgpu_buffer_rsrc_t s2_out = make_rsrc(s2, ADAM ? bytes : 0u);
-    const __amdgpu_buffer_rsrc_t m_out = make_rsrc(m, MEAN == CMN_MEAN_TO_MEAN_GRADS ? bytes : 0u);
+    __device__ __forceinline__ TileView(const cmn_tile &tl, const void *const *grad_cols, float *const *param_ptrs,
+                                        float *const *s1_ptrs, float *const *s2_ptrs, float *const *mean_ptrs, int K) {
+        const int t = tl.tensor;
+        e0 = tl.e0; len = tl.len; s = tl.start_rank; chunk = tl.chunk;
+        gcol = grad_cols + size_t(t) * size_t(K);
+        p = param_ptrs[t] + e0;
+        s1 = s1_ptrs[t] + e0;
+        s2 = ADAM ? s2_ptrs[t] + e0 : nullptr;
+        m = USE_MEAN_TENSOR ? mean_ptrs[t] + e0 : nullptr;
+        head = tl.head[head_index<SRC, MEAN, OPT>()];
+        if (head < 0 || head > len) head = len;
+        nvec = (len - head) / VEC;
+        tail0 = head + nvec * VEC;
+    }
 
-    for (int vi = threadIdx.x; vi < nvec; vi += kBlock) {
-        const unsigned e = unsigned(head + vi * VEC);
-        float gb[VEC];
-        if (SRC == SRC_MEAN) {
-            const f32x4 g = load_vec<f32x4>(m + e);
+    // averaged gradient of the 16-byte vector at element e: fold of the K replicas, times 1/K
+    template <int U>
+    __device__ __forceinline__ void fold(float (&gb)[G::VEC], unsigned e, const float *const *scale_ptrs, int K,
+                                         float inv_k) const {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) gb[i] = g[i];
-        } else {
+        for (int i = 0; i < G::VEC; ++i) gb[i] = sum_identity();
+        fold_all<DT, U>(
+            gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + e0 + e; },
+            [&](int j) { return scale_ptrs[ring_rank(s, j, K)][chunk]; });
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
-            fold_all<DT, U>(
-                gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + tl.e0 + e; },
-                [&](int j) { return scale_ptrs[ring_rank(s, j, K)][tl.chunk]; });
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
-        }
-        // parameter and state are fetched only now, close to the stores that rewrite them
+        for (int i = 0; i < G::VEC; ++i) gb[i] = gb[i] * inv_k;
+    }
+
+    // optimizer on the vector at element e, parameter and state fetched here, results (and the
+    // averaged gradient, where asked for) stored write-through
+    template <bool WT = true>
+    __device__ __forceinline__ void apply(const float (&gb)[VEC], unsigned e, int K, const OptArgs &o) const {
+        const unsigned bytes = unsigned(len) * 4u;
+        const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, bytes);
+        const __amdgpu_buffer_rsrc_t s1_out = make_rsrc(s1, bytes);
+        const __amdgpu_buffer_rsrc_t s2_out = make_rsrc(s2, ADAM ? bytes : 0u);
+        const __amdgpu_buffer_rsrc_t m_out = make_rsrc(m, MEAN == CMN_MEAN_TO_MEAN_GRADS ? bytes : 0u);
         f32x4 pv[VEC / 4], s1v[VEC / 4], s2v[VEC / 4];
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
@@ -80,7 +82,6 @@ __global__ __launch_bounds__(kBlock) void k_step(
             s1v[q] = load_vec<f32x4>(s1 + e + 4 * q);
             if (ADAM) s2v[q] = load_vec<f32x4>(s2 + e + 4 * q);
         }
-
 #pragma unroll
         for (int q = 0; q < VEC / 4; ++q) {
 #pragma unroll
@@ -91,46 +92,128 @@ __global__ __launch_bounds__(kBlock) void k_step(
                 if (ADAM) s2v[q][i] = b;
             }
             if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS)
-                store_through(m_out, (e + 4 * q) * 4u, f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]});
-            if (ADAM) store_through(s2_out, (e + 4 * q) * 4u, s2v[q]);
-            store_through(s1_out, (e + 4 * q) * 4u, s1v[q]);
-            store_through(p_out, (e + 4 * q) * 4u, pv[q]);
+                store_out<WT>(m_out, (e + 4 * q) * 4u, f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]});
+            if (ADAM) store_out<WT>(s2_out, (e + 4 * q) * 4u, s2v[q]);
+            store_out<WT>(s1_out, (e + 4 * q) * 4u, s1v[q]);
+            store_out<WT>(p_out, (e + 4 * q) * 4u, pv[q]);
         }
         if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
-            // every gradient of this vector has been read above; hand the average to each replica
-            const raw avg = G::encode_vec(gb);
+            // every gradient of this vector has been read before; hand the average to each replica
+            const typename G::raw avg = G::encode_vec(gb);
             for (int k = 0; k < K; ++k) {
-                elem *dst = static_cast<elem *>(const_cast<void *>(gcol[k])) + tl.e0;
+                elem *dst = static_cast<elem *>(const_cast<void *>(gcol[k])) + e0;
                 store_through(make_rsrc(dst, unsigned(len) * unsigned(sizeof(elem))), e * unsigned(sizeof(elem)), avg);
             }
         }
     }
 
-    // ragged head and tail of the tile (or the whole tile when its streams share no alignment)
-    const int n_single = head + (len - tail0);
-    for (int i = threadIdx.x; i < n_single; i += kBlock) {
-        const int e = i < head ? i : tail0 + (i - head);
-        float gb;
-        if (SRC == SRC_MEAN) {
-            gb = m[e];
-        } else {
-            float acc = sum_identity();
-            for (int j = 0; j < K; ++j) {
-                const int r = ring_rank(s, j, K);
-                acc = acc + G::decode(static_cast<const elem *>(gcol[r])[tl.e0 + e],
-                                      DT == CMN_I8S ? scale_ptrs[r][tl.chunk] : 1.0f);
+    // ragged head and tail of the tile (or the whole tile when its streams share no alignment):
+    // one element per thread, start to finish
+    __device__ __forceinline__ void ragged(const float *const *scale_ptrs, int K, float inv_k, const OptArgs &o) const {
+        const int n_single = head + (len - tail0);
+        for (int i = threadIdx.x; i < n_single; i += kBlock) {
+            const int e = i < head ? i : tail0 + (i - head);
+            float gb;
+            if (SRC == SRC_MEAN) {
+                gb = m[e];
+            } else {
+                float acc = sum_identity();
+                for (int j = 0; j < K; ++j) {
+                    const int r = ring_rank(s, j, K);
+                    acc = acc + G::decode(static_cast<const elem *>(gcol[r])[e0 + e],
+                                          DT == CMN_I8S ? scale_ptrs[r][chunk] : 1.0f);
+                }
+                gb = acc * inv_k;
             }
-            gb = acc * inv_k;
+            float pi = p[e], a = s1[e], b = ADAM ? s2[e] : 0.0f;
+            opt_update<OPT>(gb, pi, a, b, o);
+            if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS) m[e] = gb;
+            if (ADAM) s2[e] = b;
+            s1[e] = a;
+            p[e] = pi;
+            if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
+                const elem avg = G::encode(gb);
+                for (int k = 0; k < K; ++k) static_cast<elem *>(const_cast<void *>(gcol[k]))[e0 + e] = avg;
+            }
         }
-        float pi = p[e], a = s1[e], b = ADAM ? s2[e] : 0.0f;
-        opt_update<OPT>(gb, pi, a, b, o);
-        if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS) m[e] = gb;
-        if (ADAM) s2[e] = b;
-        s1[e] = a;
-        p[e] = pi;
-        if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
-            const elem avg = G::encode(gb);
-            for (int k = 0; k < K; ++k) static_cast<elem *>(const_cast<void *>(gcol[k]))[tl.e0 + e] = avg;
+    }
+};
+
+// Streaming kernel: one workgroup per tile, everything in one go.
+// U = gradient vectors requested back to back before the first one is consumed.
+template <int DT, int U, int SRC, int MEAN, int OPT>
+__global__ __launch_bounds__(kBlock) void k_step(
+    const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
+    float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
+    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
+    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
+    using TV = TileView<DT, SRC, MEAN, OPT>;
+    constexpr int VEC = TV::VEC;
+    const TV tv(tiles[blockIdx.x], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+    for (int vi = threadIdx.x; vi < tv.nvec; vi += kBlock) {
+        const unsigned e = unsigned(tv.head + vi * VEC);
+        float gb[VEC];
+        if constexpr (SRC == SRC_MEAN) {
+            const f32x4 g = load_vec<f32x4>(tv.m + e);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) gb[i] = g[i];
+        } else {
+            tv.template fold<U>(gb, e, scale_ptrs, K, inv_k);
+        }
+        tv.apply(gb, e, K, o);
+    }
+    tv.ragged(scale_ptrs, K, inv_k, o);
+}
+
+// Two-phase persistent kernel for the fused step.  Mixing even a few stores into a saturated
+// read stream slows the reads on MI355X by far more than the stores' byte share, so the
+// work is ordered to keep them apart in time: a workgroup first folds the gradients of up
+// to M of its tiles (pure reads) and parks the averaged gradients in registers, then
+// updates the parameters and optimizer state of those tiles (a short in-place read+write
+// burst).  All workgroups start together and run at the same rate, so the phases separate
+// chip-wide without any barrier; results do not depend on it.  A tile is exactly one
+// 16-byte vector per thread here (tile_elems == kBlock * VEC).
+constexpr int kStashFloats = 200;  // averaged-gradient floats a thread parks between the phases
+
+template <int DT, int U, int MEAN, int OPT>
+__global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
+    const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
+    float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
+    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
+    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int n_tiles) {
+    using TV = TileView<DT, SRC_FOLD, MEAN, OPT>;
+    constexpr int VEC = TV::VEC;
+    constexpr int M = kStashFloats / VEC;
+    const int W = gridDim.x;
+    for (int tile0 = blockIdx.x; tile0 < n_tiles; tile0 += W * M) {
+        f32x4 gbar[M][VEC / 4];
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const int ti = tile0 + m * W;
+            if (ti < n_tiles) {
+                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                float gb[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) gb[i] = 0.0f;
+                if (int(threadIdx.x) < tv.nvec)
+                    tv.template fold<U>(gb, unsigned(tv.head + threadIdx.x * VEC), scale_ptrs, K, inv_k);
+#pragma unroll
+                for (int q = 0; q < VEC / 4; ++q) gbar[m][q] = f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]};
+                tv.ragged(scale_ptrs, K, inv_k, o);
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const int ti = tile0 + m * W;
+            if (ti < n_tiles) {
+                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                if (int(threadIdx.x) < tv.nvec) {
+                    float gb[VEC];
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) gb[i] = gbar[m][i / 4][i % 4];
+                    tv.template apply<false>(gb, unsigned(tv.head + threadIdx.x * VEC), K, o);
+                }
+            }
         }
     }
 }
@@ -144,6 +227,20 @@ inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_co
                        ws_ptr<float *const>(p, p->ws.vel_ptrs), ws_ptr<float *const>(p, p->ws.state2_ptrs),
                        ws_ptr<float *const>(p, p->ws.mean_ptrs), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
                        p->K, 1.0f / float(p->K), o);
+}
+
+template <int DT, int MEAN, int OPT>
+inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o,
+                               hipStream_t s) {
+    constexpr int U = 8;
+    const int64_t resident = int64_t(2) * p->n_cus;        // 2 workgroups per compute unit at 256 VGPRs
+    const unsigned grid = unsigned(tile_count < resident ? tile_count : resident);
+    hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
+                       ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
+                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<float *const>(p, p->ws.param_ptrs),
+                       ws_ptr<float *const>(p, p->ws.vel_ptrs), ws_ptr<float *const>(p, p->ws.state2_ptrs),
+                       ws_ptr<float *const>(p, p->ws.mean_ptrs), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
+                       p->K, 1.0f / float(p->K), o, int(tile_count));
 }
 
 // Fused step (SRC_FOLD) over tensors [t0, t1): validation shared by the SGD and Adam entry points.
@@ -163,7 +260,16 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-#define CMN_STEP_CASE(DT, MEAN) launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s)
+    // Measured on MI355X: the two-phase kernel wins from K = 8 replicas on (below that a thread
+    // has too few loads in flight at two waves per SIMD) and loses for int8 storage, whose decode
+    // arithmetic wants the streaming kernel's higher occupancy.
+    const bool two_phase = plan->two_phase && plan->K >= 8 && plan->dtype != CMN_I8S &&
+                           plan->tile_elems == kBlock * vec_elems(plan->dtype);
+#define CMN_STEP_CASE(DT, MEAN)                                                  \
+    do {                                                                         \
+        if (two_phase) launch_k_two_phase<DT, MEAN, OPT>(plan, b, n, o, s);      \
+        else launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s);           \
+    } while (0)
 #define CMN_STEP_DTYPE(DT)                                                                  \
     do {                                                                                    \
         if (mean_dest == CMN_MEAN_NONE) CMN_STEP_CASE(DT, CMN_MEAN_NONE);                   \
