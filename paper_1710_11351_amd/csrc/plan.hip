@@ -120,6 +120,25 @@ void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *p
     });
 }
 
+int device_compute_units() {
+    static const int cached = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            return cus;
+        return 256;
+    }();
+    return cached;
+}
+
+bool prefer_two_phase(const cmn_plan *p) {
+    static const bool forced_stream = [] {
+        const char *k = std::getenv("CMN_STEP_KERNEL");
+        return k && std::strcmp(k, "stream") == 0;
+    }();
+    return !forced_stream && p->K >= 8 && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
+}
+
 int check_launch(const cmn_plan *p) {
     if (!p) return CMN_ENULL;
     if (!p->bound) return CMN_EUNBOUND;
@@ -279,14 +298,6 @@ int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_p
     p->have_mean = mean_grad_ptrs != nullptr;
     p->have_state2 = false;
     p->have_scales = false;
-    {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-            p->n_cus = cus;
-        const char *k = std::getenv("CMN_STEP_KERNEL");   // tuning knob: "stream" selects the one-pass kernel
-        p->two_phase = !(k && std::strcmp(k, "stream") == 0);
-    }
     if (int rc2 = upload_image(p, dev_workspace, static_cast<hipStream_t>(stream))) return rc2;
     p->dev_ws = static_cast<char *>(dev_workspace);
     p->bound = true;

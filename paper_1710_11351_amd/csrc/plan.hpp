@@ -17,6 +17,10 @@ constexpr int kBlock = 256;  // threads per workgroup of every kernel (4 wavefro
 // Elements of one cmn_tile at most: kBlock threads x one 16-byte vector x kTileIters.
 constexpr int kTileIters = 1;
 
+// Floats a thread of a two-phase kernel parks in registers between its read phase and its
+// write phase (leaves ~50 of the 256 registers available at two waves per SIMD for the fold).
+constexpr int kStashFloats = 200;
+
 inline int elem_bytes(int dtype) { return dtype == CMN_F32 ? 4 : dtype == CMN_I8S ? 1 : 2; }
 inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }
 
@@ -39,8 +43,6 @@ struct WorkspaceLayout {
 struct cmn_plan {
     int T = 0, K = 1, C = 1, align_bytes = 256, dtype = CMN_F32, ring_rotate = 1;
     int tile_elems = 0;
-    int n_cus = 256;         // compute units of the device the plan was bound on
-    bool two_phase = true;   // fused steps use the two-phase persistent kernel (CMN_STEP_KERNEL=stream: the one-pass one)
     std::vector<int64_t> numel;  // [T]
     std::vector<int64_t> off;    // [T+1]
     int64_t N = 0, chunk_elems = 0, L = 0, n_tiles = 0;
@@ -61,6 +63,12 @@ void build_tiles(const cmn_plan &p, const void *const *grad_ptrs, void *const *p
 
 // Shared argument checks of the kernel entry points.
 int check_launch(const cmn_plan *p);
+
+// Compute units of the current device (cached) and the kernel-choice rule measured on MI355X:
+// the two-phase kernels win from K = 8 replicas on and lose for int8 storage.
+// CMN_STEP_KERNEL=stream in the environment forces the one-pass kernels (A/B runs, tests).
+int device_compute_units();
+bool prefer_two_phase(const cmn_plan *p);
 
 template <typename T>
 inline T *ws_ptr(const cmn_plan *p, size_t byte_off) {

@@ -1,7 +1,10 @@
 // cmn_ring_reduce: K packed replica buffers [K][L] -> one float32 sum [L].
-// A workgroup owns one tile of one ring chunk, so the fold order (which replica
-// is read first) is uniform over the workgroup and every output vector is
-// produced once by one thread: K streaming reads, one streaming write.
+// A workgroup works on one tile of one ring chunk at a time, so the fold order (which
+// replica is read first) is uniform over the workgroup and every output vector is
+// produced once by one thread: K streaming reads, one streaming write.  Two kernels:
+// one-pass (a workgroup per tile) and, from K = 8 on, two-phase persistent (a workgroup
+// folds many tiles into registers, then writes them), which keeps the write stream out
+// of the read stream's way on MI355X.
 #include <hip/hip_runtime.h>
 
 #include "device_util.hpp"
@@ -51,6 +54,55 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
     }
 }
 
+template <int DT, int U>
+__global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
+    const void *__restrict__ packed, float *__restrict__ reduced, const float *const *__restrict__ scale_ptrs,
+    long long L, long long chunk_elems, int tiles_per_chunk, int K, int ring_rotate, int n_tiles) {
+    using G = GradT<DT>;
+    using elem = typename G::elem;
+    constexpr int VEC = G::VEC;
+    constexpr int TILE = kBlock * VEC;
+    constexpr int M = kStashFloats / VEC;
+    const int W = gridDim.x;
+    const int e = threadIdx.x * VEC;
+    for (int tile0 = blockIdx.x; tile0 < n_tiles; tile0 += W * M) {
+        f32x4 stash[M][VEC / 4];
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const int g = tile0 + m * W;
+            if (g < n_tiles) {
+                const int c = g / tiles_per_chunk, tile = g - c * tiles_per_chunk;
+                const int s = ring_rotate ? c % K : 0;
+                const int in_chunk = int(min((long long)TILE, chunk_elems - (long long)tile * TILE));
+                const elem *src = static_cast<const elem *>(packed) + c * chunk_elems + (long long)tile * TILE;
+                float acc[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
+                if (e < in_chunk)
+                    fold_all<DT, U>(
+                        acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
+                        [&](int j) { return scale_ptrs[ring_rank(s, j, K)][c]; });
+#pragma unroll
+                for (int q = 0; q < VEC / 4; ++q) stash[m][q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            const int g = tile0 + m * W;
+            if (g < n_tiles) {
+                const int c = g / tiles_per_chunk, tile = g - c * tiles_per_chunk;
+                const int in_chunk = int(min((long long)TILE, chunk_elems - (long long)tile * TILE));
+                float *dst = reduced + c * chunk_elems + (long long)tile * TILE;
+                const __amdgpu_buffer_rsrc_t out = make_rsrc(dst, unsigned(in_chunk) * 4u);
+                if (e < in_chunk) {
+#pragma unroll
+                    for (int q = 0; q < VEC / 4; ++q) store_back(out, unsigned(e + 4 * q) * 4u, stash[m][q]);
+                }
+            }
+        }
+    }
+}
+
 }  // namespace cmn
 
 using namespace cmn;
@@ -73,7 +125,23 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
         if (!plan->bound || !plan->have_scales) return CMN_EUNBOUND;
         scales = ws_ptr<const float *const>(plan, plan->ws.scale_ptrs);
     }
-    if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE(CMN_F32);
+    // With one write per K reads the two-phase kernel only pays while all tiles fit one or two
+    // rounds of the persistent grid (ResNet-50: 507 vs 551 us); over more rounds the workgroups
+    // drift out of phase and the one-pass kernel is as good or better (VGG-16: 1698 vs 1679 us).
+    const long long n_tiles_all = tpc * plan->C;
+    const long long slots = 2LL * device_compute_units() * (kStashFloats / vec_elems(plan->dtype));
+    if (prefer_two_phase(plan) && kReduceIters == 1 && n_tiles_all <= 2 * slots) {
+        const long long n_tiles = n_tiles_all, resident = 2LL * device_compute_units();
+        const dim3 pgrid(unsigned(n_tiles < resident ? n_tiles : resident));
+#define CMN_LAUNCH_REDUCE2(DT)                                                                               \
+    hipLaunchKernelGGL((k_ring_reduce_two_phase<DT, 8>), pgrid, dim3(kBlock), 0, s, packed, reduced, scales,  \
+                       (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate, \
+                       int(n_tiles))
+        if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE2(CMN_F32);
+        else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE2(CMN_F16);
+        else CMN_LAUNCH_REDUCE2(CMN_BF16);
+#undef CMN_LAUNCH_REDUCE2
+    } else if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE(CMN_F32);
     else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE(CMN_F16);
     else if (plan->dtype == CMN_BF16) CMN_LAUNCH_REDUCE(CMN_BF16);
     else CMN_LAUNCH_REDUCE(CMN_I8S);

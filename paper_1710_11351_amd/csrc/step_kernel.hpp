@@ -173,8 +173,6 @@ __global__ __launch_bounds__(kBlock) void k_step(
 // burst).  All workgroups start together and run at the same rate, so the phases separate
 // chip-wide without any barrier; results do not depend on it.  A tile is exactly one
 // 16-byte vector per thread here (tile_elems == kBlock * VEC).
-constexpr int kStashFloats = 200;  // averaged-gradient floats a thread parks between the phases
-
 template <int DT, int U, int MEAN, int OPT>
 __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
@@ -233,7 +231,7 @@ template <int DT, int MEAN, int OPT>
 inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o,
                                hipStream_t s) {
     constexpr int U = 8;
-    const int64_t resident = int64_t(2) * p->n_cus;        // 2 workgroups per compute unit at 256 VGPRs
+    const int64_t resident = int64_t(2) * device_compute_units();   // 2 workgroups per compute unit at 256 VGPRs
     const unsigned grid = unsigned(tile_count < resident ? tile_count : resident);
     hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
                        ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
@@ -260,11 +258,7 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // Measured on MI355X: the two-phase kernel wins from K = 8 replicas on (below that a thread
-    // has too few loads in flight at two waves per SIMD) and loses for int8 storage, whose decode
-    // arithmetic wants the streaming kernel's higher occupancy.
-    const bool two_phase = plan->two_phase && plan->K >= 8 && plan->dtype != CMN_I8S &&
-                           plan->tile_elems == kBlock * vec_elems(plan->dtype);
+    const bool two_phase = prefer_two_phase(plan);
 #define CMN_STEP_CASE(DT, MEAN)                                                  \
     do {                                                                         \
         if (two_phase) launch_k_two_phase<DT, MEAN, OPT>(plan, b, n, o, s);      \
