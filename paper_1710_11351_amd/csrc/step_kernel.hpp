@@ -1,9 +1,12 @@
-// The tensor-space kernel behind cmn_allreduce_step, cmn_allreduce_adam_step, their
+// The tensor-space kernels behind cmn_allreduce_step, cmn_allreduce_adam_step, their
 // _range forms, cmn_momentum_sgd and cmn_adam.  A tile names a run of elements of one
 // tensor inside one ring chunk; every thread owns one 16-byte gradient vector of it.
 //   SRC_FOLD: read the K replicas' vectors in the chunk's fold order, sum, scale by 1/K
 //   SRC_MEAN: read the averaged gradient from the bound mean-gradient tensor
 // then apply the optimizer to p and its state in place.  No packed buffer exists.
+// TileView holds the per-tile work (fold, apply, ragged elements); k_step does it in one
+// pass with a workgroup per tile, k_step_two_phase with a persistent grid that reads
+// first and writes afterwards.  Both give identical bits.
 #pragma once
 
 #include <hip/hip_runtime.h>
