@@ -164,7 +164,8 @@ int cmn_scale_unpack(const cmn_plan *plan, const float *reduced /* device [L] */
  * rate (written mu in the paper's Section 2.1), mu the momentum coefficient. */
 int cmn_momentum_sgd(const cmn_plan *plan, float lr, float mu, float wd, void *stream);
 
-/* S1..S5 fused into one kernel launch with no intermediate buffer: for every element
+/* S1..S5 fused into one pass over HBM with no intermediate buffer (one kernel launch for
+ * lists up to about 26 M elements, a few back-to-back launches beyond): for every element
  * read the K replicas' gradients in the fixed order, sum, multiply by 1.0f/(float)K,
  * apply the MomentumSGD rule above to p and v in place, and put the averaged gradient
  * where mean_dest (a cmn_mean_dest; 0 and 1 keep the meaning of a boolean) says.

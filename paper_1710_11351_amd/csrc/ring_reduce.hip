@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
 template <int DT, int U>
 __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
     const void *__restrict__ packed, float *__restrict__ reduced, const float *const *__restrict__ scale_ptrs,
-    long long L, long long chunk_elems, int tiles_per_chunk, int K, int ring_rotate, int n_tiles) {
+    long long L, long long chunk_elems, int tiles_per_chunk, int K, int ring_rotate, int tile_begin, int n_tiles) {
     using G = GradT<DT>;
     using elem = typename G::elem;
     constexpr int VEC = G::VEC;
@@ -65,7 +65,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
     constexpr int M = kStashFloats / VEC;
     const int W = gridDim.x;
     const int e = threadIdx.x * VEC;
-    for (int tile0 = blockIdx.x; tile0 < n_tiles; tile0 += W * M) {
+    // this launch owns the (chunk, tile) pairs numbered [tile_begin, n_tiles)
+    for (int tile0 = tile_begin + blockIdx.x; tile0 < n_tiles; tile0 += W * M) {
         f32x4 stash[M][VEC / 4];
 #pragma unroll
         for (int m = 0; m < M; ++m) {
@@ -125,21 +126,22 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
         if (!plan->bound || !plan->have_scales) return CMN_EUNBOUND;
         scales = ws_ptr<const float *const>(plan, plan->ws.scale_ptrs);
     }
-    // With one write per K reads the two-phase kernel only pays while all tiles fit one or two
-    // rounds of the persistent grid (ResNet-50: 507 vs 551 us); over more rounds the workgroups
-    // drift out of phase and the one-pass kernel is as good or better (VGG-16: 1698 vs 1679 us).
-    const long long n_tiles_all = tpc * plan->C;
-    const long long slots = 2LL * device_compute_units() * (kStashFloats / vec_elems(plan->dtype));
-    if (prefer_two_phase(plan) && kReduceIters == 1 && n_tiles_all <= 2 * slots) {
-        const long long n_tiles = n_tiles_all, resident = 2LL * device_compute_units();
-        const dim3 pgrid(unsigned(n_tiles < resident ? n_tiles : resident));
-#define CMN_LAUNCH_REDUCE2(DT)                                                                               \
-    hipLaunchKernelGGL((k_ring_reduce_two_phase<DT, 8>), pgrid, dim3(kBlock), 0, s, packed, reduced, scales,  \
-                       (long long)plan->L, (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate, \
-                       int(n_tiles))
-        if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE2(CMN_F32);
-        else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE2(CMN_F16);
-        else CMN_LAUNCH_REDUCE2(CMN_BF16);
+    if (prefer_two_phase(plan) && kReduceIters == 1) {
+        // one launch per round of the persistent grid, tiles spread evenly (a kernel boundary
+        // realigns the phases of the workgroups)
+        const long long n_tiles = tpc * plan->C, resident = 2LL * device_compute_units();
+        const long long slots = resident * (kStashFloats / vec_elems(plan->dtype));
+        const long long n_launch = (n_tiles + slots - 1) / slots, per_launch = (n_tiles + n_launch - 1) / n_launch;
+#define CMN_LAUNCH_REDUCE2(DT)                                                                                  \
+    for (long long b0 = 0; b0 < n_tiles; b0 += per_launch) {                                                    \
+        const long long e0 = b0 + per_launch < n_tiles ? b0 + per_launch : n_tiles, cnt = e0 - b0;              \
+        hipLaunchKernelGGL((k_ring_reduce_two_phase<DT, 8>), dim3(unsigned(cnt < resident ? cnt : resident)),   \
+                           dim3(kBlock), 0, s, packed, reduced, scales, (long long)plan->L,                     \
+                           (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate, int(b0), int(e0)); \
+    }
+        if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE2(CMN_F32)
+        else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE2(CMN_F16)
+        else CMN_LAUNCH_REDUCE2(CMN_BF16)
 #undef CMN_LAUNCH_REDUCE2
     } else if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE(CMN_F32);
     else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE(CMN_F16);
