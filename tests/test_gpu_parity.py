@@ -256,7 +256,8 @@ def test_config3_resnet50_k32_adam_full_size():
     run_parity(wl.config(3), steps=2, opt="adam", staged=False)
 
 
-def test_range_steps_replayed_from_a_hip_graph_match_eager():
+@pytest.mark.parametrize("K", [4, 8])            # one-pass kernel / two-phase persistent kernel
+def test_range_steps_replayed_from_a_hip_graph_match_eager(K):
     """A launch-bound sequence of small per-layer-group steps captured once into a HIP graph
     and replayed must give the same bits as eager launches, on every replay (the library
     only enqueues kernels on the caller's stream: nothing else ends up in the graph)."""
@@ -264,7 +265,7 @@ def test_range_steps_replayed_from_a_hip_graph_match_eager():
     from paper_1710_11351_amd import binding as B
     from parity_util import DeviceCase, assert_bit_equal, gen_all_grads
     numel = [4096, 64, 64, 36864, 256, 256, 9408, 1000]
-    c = wl.custom_config(numel, K=4, n_chunks=4, cfg=87)
+    c = wl.custom_config(numel, K=K, n_chunks=4, cfg=87)
     eager, graphed = DeviceCase(c), DeviceCase(c)
     p0, v0 = wl.gen_params(c), wl.gen_velocity(c)
     for dc in (eager, graphed):
