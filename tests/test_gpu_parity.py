@@ -338,3 +338,8 @@ def test_buffer_arguments_are_validated_on_a_bound_plan():
     assert B.cmn_allreduce_step(dc2.plan.h, .1, .9, 0., B.CMN_MEAN_TO_MEAN_GRADS) == B.CMN_EUNBOUND
     assert B.cmn_allreduce_step(dc2.plan.h, .1, .9, 0., B.CMN_MEAN_NONE) == B.CMN_OK
     torch.cuda.synchronize()
+
+
+def test_a_thousand_replicas():
+    c = wl.custom_config([3000, 1, 2100], K=1000, n_chunks=7, cfg=78)
+    run_parity(c, steps=1)

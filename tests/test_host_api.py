@@ -203,3 +203,54 @@ def test_plain_c_client_links_and_runs(tmp_path):
                     f"-Wl,-rpath,{libdir}"], check=True)
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0 and "abi_check ok" in r.stdout, r.stdout + r.stderr
+
+
+# ------------------------------------------------------------------ property test of the tile table
+from hypothesis import given, settings, strategies as st
+
+
+@settings(max_examples=120, deadline=None)
+@given(numel=st.lists(st.sampled_from([0, 1, 3, 7, 64, 100, 1023, 1024, 1025, 4097, 20000]), min_size=1, max_size=9),
+       K=st.integers(1, 9), C=st.integers(1, 7), dtype=st.sampled_from(["f32", "f16", "bf16", "i8s"]),
+       rot=st.integers(0, 1), mis=st.lists(st.integers(0, 7), min_size=4, max_size=4))
+def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis):
+    """Coverage, chunk confinement, fold start and vector alignment of every tile, for arbitrary
+    lists, replica counts, chunk counts, storage types and base misalignments."""
+    eb = {"f32": 4, "f16": 2, "bf16": 2, "i8s": 1}[dtype]
+    vec = 16 // eb
+    p = B.Plan(numel, K, C, 256, dtype, rot)
+    base = 1 << 24
+    grads = []
+    for k in range(K):
+        g, base = _fake_ptrs(numel, base, eb, misalign=mis[0] if k % 2 == 0 else mis[1])
+        grads.append(g)
+    pp, base = _fake_ptrs(numel, base, 4, misalign=mis[2])
+    vp, base = _fake_ptrs(numel, base, 4, misalign=mis[2])
+    mp, base = _fake_ptrs(numel, base, 4, misalign=mis[3])
+    sp, base = _fake_ptrs(numel, base, 4, misalign=mis[2])
+    rc, tiles = B.cmn_plan_describe_tiles(p.h, [a for g in grads for a in g], pp, vp, mp, sp)
+    assert rc == B.CMN_OK and len(tiles) == p.tile_count
+    off = np.concatenate([[0], np.cumsum(numel)])
+    covered = [0] * len(numel)
+    streams = {B.CMN_HEAD_STEP: lambda t: [(g[t], eb) for g in grads] + [(pp[t], 4), (vp[t], 4)],
+               B.CMN_HEAD_STEP_MEAN: lambda t: [(g[t], eb) for g in grads] + [(pp[t], 4), (vp[t], 4), (mp[t], 4)],
+               B.CMN_HEAD_SGD: lambda t: [(mp[t], 4), (pp[t], 4), (vp[t], 4)],
+               B.CMN_HEAD_ADAM: lambda t: [(g[t], eb) for g in grads] + [(pp[t], 4), (vp[t], 4), (sp[t], 4)],
+               B.CMN_HEAD_ADAM_MEAN: lambda t: [(g[t], eb) for g in grads] + [(pp[t], 4), (vp[t], 4), (sp[t], 4), (mp[t], 4)],
+               B.CMN_HEAD_ADAM_OPT: lambda t: [(mp[t], 4), (pp[t], 4), (vp[t], 4), (sp[t], 4)]}
+    for tl in tiles:
+        t, e0, ln, c = int(tl["tensor"]), int(tl["e0"]), int(tl["len"]), int(tl["chunk"])
+        assert 0 < ln <= 256 * vec and covered[t] == e0
+        covered[t] += ln
+        assert (off[t] + e0) // p.chunk_elems == c == (off[t] + e0 + ln - 1) // p.chunk_elems and c < C
+        assert int(tl["start_rank"]) == (c % K if rot else 0)
+        for variant, lst in streams.items():
+            h = int(tl["head"][variant])
+            w = 4 if variant in (B.CMN_HEAD_SGD, B.CMN_HEAD_ADAM_OPT) else vec
+            assert -1 <= h < w
+            if h >= 0:   # element e0 + h starts a 16-byte vector on every stream of the variant
+                for addr, es in lst(t):
+                    assert (addr + (e0 + h) * es) % 16 == 0
+            else:        # no head makes all streams 16-byte aligned at once
+                assert not any(all((addr + (e0 + hh) * es) % 16 == 0 for addr, es in lst(t)) for hh in range(w))
+    assert covered == list(numel)
