@@ -27,10 +27,24 @@ def sources():
 
 
 def build_lib(verbose: bool = False, extra_flags=()) -> str:
-    cmd = ["hipcc", *HIPCC_FLAGS, *extra_flags, *sources(), "-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    """Compile every csrc/*.hip to an object (in parallel) and link libcmn.so."""
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + list(extra_flags)
+    with tempfile.TemporaryDirectory(prefix="cmn_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            cmd = ["hipcc", *flags, "-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            objs = list(ex.map(compile_one, sources()))
+        link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
     return LIB
 
 

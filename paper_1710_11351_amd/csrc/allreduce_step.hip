@@ -1,5 +1,6 @@
-// Entry points of the fused aggregation + update step (S1..S5 in one pass over HBM):
-// MomentumSGD and Adam, over the whole tensor list or a range of it.
+// Entry points of the fused aggregation + update step (S1..S5 in one pass over HBM)
+// with MomentumSGD, over the whole tensor list or a range of it.  (The Adam entry points
+// live in allreduce_adam_step.hip so that the two sets of kernel variants build in parallel.)
 // HBM traffic per element: K gradient reads + parameter and optimizer state read and
 // written (+ the averaged gradient, once or K times, if asked for).
 #include <cmath>
@@ -17,18 +18,4 @@ extern "C" int cmn_allreduce_step_range(const cmn_plan *plan, int tensor_begin, 
 extern "C" int cmn_allreduce_step(const cmn_plan *plan, float lr, float mu, float wd, int mean_dest, void *stream) {
     if (!plan) return CMN_ENULL;
     return cmn_allreduce_step_range(plan, 0, plan->T, lr, mu, wd, mean_dest, stream);
-}
-
-extern "C" int cmn_allreduce_adam_step_range(const cmn_plan *plan, int tensor_begin, int tensor_end, float alpha,
-                                             float beta1, float beta2, float eps, float wd, int t, int mean_dest,
-                                             void *stream) {
-    if (t < 1) return plan ? CMN_EINVAL : CMN_ENULL;
-    const OptArgs o{adam_step_size(alpha, beta1, beta2, t), 1.0f - beta1, 1.0f - beta2, eps, wd};
-    return launch_fused<OPT_ADAM>(plan, tensor_begin, tensor_end, mean_dest, o, stream);
-}
-
-extern "C" int cmn_allreduce_adam_step(const cmn_plan *plan, float alpha, float beta1, float beta2, float eps,
-                                       float wd, int t, int mean_dest, void *stream) {
-    if (!plan) return CMN_ENULL;
-    return cmn_allreduce_adam_step_range(plan, 0, plan->T, alpha, beta1, beta2, eps, wd, t, mean_dest, stream);
 }
