@@ -117,26 +117,32 @@ def test_bf16_storage_within_8e3_of_unquantised_fp32():
         assert np.max(np.abs(got[t] - want)) > 0
 
 
-def test_special_values_propagate():
+@pytest.mark.parametrize("K", [2, 8])             # one-pass kernel / two-phase persistent kernel
+def test_special_values_propagate(K):
     import torch
     from paper_1710_11351_amd import binding as B
     n = 1024
-    plan = B.Plan([n], 2, 2)
+    plan = B.Plan([n], K, 2)
     a = np.zeros(n, np.float32); b = np.zeros(n, np.float32)
     a[0], b[0] = np.inf, 1.0
     a[1], b[1] = np.inf, -np.inf
     a[2], b[2] = -0.0, -0.0
     a[3], b[3] = 1e-45, 1e-45
     a[4], b[4] = 1e-40, 2e-40
-    g = [[torch.from_numpy(a).cuda()], [torch.from_numpy(b).cuda()]]
+    rest = np.zeros(n, np.float32); rest[2] = -0.0                      # the other K-2 replicas add nothing
+    g = [[torch.from_numpy(a).cuda()], [torch.from_numpy(b).cuda()]] + [[torch.from_numpy(rest).cuda()] for _ in range(K - 2)]
     p = [torch.zeros(n, device="cuda")]; v = [torch.zeros(n, device="cuda")]; m = [torch.ones(n, device="cuda")]
     plan.bind(g, p, v, m)
     plan.allreduce_step(1.0, 0.0, 0.0, write_mean_grad=True)
     out = m[0].cpu().numpy()
+    s = np.float32(1.0) / np.float32(K)
     assert out[0] == np.inf and np.isnan(out[1])
     assert out[2] == 0 and np.signbit(out[2])
-    assert out[3] == np.float32(1e-45) and out[4] == (np.float32(1e-40) + np.float32(2e-40)) * np.float32(0.5)
+    assert out[3] == (np.float32(1e-45) + np.float32(1e-45)) * s         # subnormals are kept, not flushed
+    assert out[4] == (np.float32(1e-40) + np.float32(2e-40)) * s and out[4] != 0
     assert not out[5:].any()
+    pv = p[0].cpu().numpy()
+    assert pv[0] == -np.inf and np.isnan(pv[1])                           # and reach the parameters
 
 
 def test_empty_plan_is_a_no_op():
