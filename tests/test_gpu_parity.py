@@ -29,6 +29,14 @@ def test_unaligned_base_pointers(dtype, misalign):
     run_parity(c, steps=2, misalign=misalign)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("misalign", [0, 1, 3])
+def test_ragged_unaligned_lists_through_the_two_phase_kernel(dtype, misalign):
+    numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3, 70000]
+    c = wl.custom_config(numel, K=10, n_chunks=7, grad_dtype=dtype, cfg=77, wd=1e-3)
+    run_parity(c, steps=2, misalign=misalign)
+
+
 def test_single_replica_is_the_plain_optimizer():
     c = wl.custom_config([3000, 100], K=1, n_chunks=1, cfg=93)
     run_parity(c, steps=2)
@@ -161,19 +169,21 @@ def test_config2_resnet50_k4_full_size():
 
 
 # ---- widened rows: bucketed (per layer group) steps, Adam, average handed back to every replica ----
+@pytest.mark.parametrize("K", [5, 8])
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("opt", ["sgd", "adam"])
-def test_bucketed_range_steps_equal_one_full_step(dtype, opt):
+def test_bucketed_range_steps_equal_one_full_step(dtype, opt, K):
     numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3, 800, 4096]
-    c = wl.custom_config(numel, K=5, n_chunks=5, grad_dtype=dtype, cfg=98, wd=1e-3)
+    c = wl.custom_config(numel, K=K, n_chunks=5, grad_dtype=dtype, cfg=98, wd=1e-3)
     run_parity(c, steps=2, staged=False, opt=opt, bucketed=True)
 
 
+@pytest.mark.parametrize("K", [6, 12])
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("misalign", [0, 3])
-def test_adam_fused_and_staged(dtype, misalign):
+def test_adam_fused_and_staged(dtype, misalign, K):
     numel = [1000, 4096, 37, 8192 + 5, 0, 64]
-    c = wl.custom_config(numel, K=6, n_chunks=3, grad_dtype=dtype, cfg=99, wd=5e-4 if misalign else 0.0)
+    c = wl.custom_config(numel, K=K, n_chunks=3, grad_dtype=dtype, cfg=99, wd=5e-4 if misalign else 0.0)
     run_parity(c, steps=3, opt="adam", misalign=misalign)
 
 
@@ -188,16 +198,17 @@ def test_range_arguments_are_validated():
     assert B.cmn_allreduce_step_range(dc.plan.h, 1, 1, .1, .9, 0., 0) == B.CMN_OK      # empty range: no-op
 
 
+@pytest.mark.parametrize("K", [5, 9])             # one-pass kernel / two-phase persistent kernel
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("misalign", [0, 1])
-def test_average_is_handed_back_to_every_replica(dtype, misalign):
+def test_average_is_handed_back_to_every_replica(dtype, misalign, K):
     """The all-gather half of the allreduce: afterwards every worker's gradient tensors hold the
     average (rounded to nearest even when the workers store binary16)."""
     import oracle
     from paper_1710_11351_amd import binding as B
     from parity_util import DeviceCase, assert_bit_equal, gen_all_grads
     numel = [3000, 0, 77, 4096, 1, 2050]
-    c = wl.custom_config(numel, K=5, n_chunks=4, grad_dtype=dtype, cfg=88, outlier_frac=0.01 if dtype == "f16" else 0.0)
+    c = wl.custom_config(numel, K=K, n_chunks=4, grad_dtype=dtype, cfg=88, outlier_frac=0.01 if dtype == "f16" else 0.0)
     dc = DeviceCase(c, misalign=misalign)
     p_o, v_o = [x.copy() for x in wl.gen_params(c)], wl.gen_velocity(c)
     dc.set_state(p_o, v_o)
