@@ -132,11 +132,7 @@ int device_compute_units() {
 }
 
 bool prefer_two_phase(const cmn_plan *p) {
-    static const bool forced_stream = [] {
-        const char *k = std::getenv("CMN_STEP_KERNEL");
-        return k && std::strcmp(k, "stream") == 0;
-    }();
-    return !forced_stream && p->K >= 8 && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
+    return !p->one_pass_only && p->K >= 8 && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
 }
 
 int check_launch(const cmn_plan *p) {
@@ -190,6 +186,7 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
         if (v >= 1 && v <= 64) iters = v;
     }
     p->tile_elems = kBlock * vec_elems(grad_dtype) * iters;
+    if (const char *k = std::getenv("CMN_STEP_KERNEL")) p->one_pass_only = std::strcmp(k, "stream") == 0;
     try {
         p->first_tile.assign(size_t(n_tensors) + 1, 0);
     } catch (...) { delete p; return CMN_ENOMEM; }

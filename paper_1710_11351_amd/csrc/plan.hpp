@@ -43,6 +43,7 @@ struct WorkspaceLayout {
 struct cmn_plan {
     int T = 0, K = 1, C = 1, align_bytes = 256, dtype = CMN_F32, ring_rotate = 1;
     int tile_elems = 0;
+    bool one_pass_only = false;  // CMN_STEP_KERNEL=stream at creation: never pick the two-phase kernels
     std::vector<int64_t> numel;  // [T]
     std::vector<int64_t> off;    // [T+1]
     int64_t N = 0, chunk_elems = 0, L = 0, n_tiles = 0;

@@ -37,6 +37,19 @@ def test_ragged_unaligned_lists_through_the_two_phase_kernel(dtype, misalign):
     run_parity(c, steps=2, misalign=misalign)
 
 
+@pytest.mark.parametrize("env", [{"CMN_STEP_KERNEL": "stream"}, {"CMN_TILE_ITERS": "2"}, {"CMN_TILE_ITERS": "5"}])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_launch_shape_knobs_do_not_change_results(monkeypatch, env, dtype):
+    """The two environment knobs read at plan creation pick another kernel or tile size; the result
+    stays the oracle's, bit for bit (K = 12 would otherwise take the two-phase kernels)."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    numel = [5, 0, 5000, 1, 64, 12345, 7, 2049, 3, 30000]
+    c = wl.custom_config(numel, K=12, n_chunks=6, grad_dtype=dtype, cfg=76, wd=1e-3)
+    run_parity(c, steps=2, misalign=1)
+    run_parity(c, steps=1, staged=True, fused=False)
+
+
 def test_single_replica_is_the_plain_optimizer():
     c = wl.custom_config([3000, 100], K=1, n_chunks=1, cfg=93)
     run_parity(c, steps=2)

@@ -212,13 +212,21 @@ from hypothesis import given, settings, strategies as st
 @settings(max_examples=120, deadline=None)
 @given(numel=st.lists(st.sampled_from([0, 1, 3, 7, 64, 100, 1023, 1024, 1025, 4097, 20000]), min_size=1, max_size=9),
        K=st.integers(1, 9), C=st.integers(1, 7), dtype=st.sampled_from(["f32", "f16", "bf16", "i8s"]),
-       rot=st.integers(0, 1), mis=st.lists(st.integers(0, 7), min_size=4, max_size=4))
-def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis):
+       rot=st.integers(0, 1), mis=st.lists(st.integers(0, 7), min_size=4, max_size=4), iters=st.sampled_from([1, 1, 2, 5]))
+def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis, iters):
     """Coverage, chunk confinement, fold start and vector alignment of every tile, for arbitrary
-    lists, replica counts, chunk counts, storage types and base misalignments."""
+    lists, replica counts, chunk counts, storage types, base misalignments and tile sizes."""
     eb = {"f32": 4, "f16": 2, "bf16": 2, "i8s": 1}[dtype]
     vec = 16 // eb
-    p = B.Plan(numel, K, C, 256, dtype, rot)
+    old = os.environ.get("CMN_TILE_ITERS")
+    os.environ["CMN_TILE_ITERS"] = str(iters)         # read by cmn_plan_create
+    try:
+        p = B.Plan(numel, K, C, 256, dtype, rot)
+    finally:
+        if old is None:
+            del os.environ["CMN_TILE_ITERS"]
+        else:
+            os.environ["CMN_TILE_ITERS"] = old
     base = 1 << 24
     grads = []
     for k in range(K):
@@ -240,7 +248,7 @@ def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis):
                B.CMN_HEAD_ADAM_OPT: lambda t: [(mp[t], 4), (pp[t], 4), (vp[t], 4), (sp[t], 4)]}
     for tl in tiles:
         t, e0, ln, c = int(tl["tensor"]), int(tl["e0"]), int(tl["len"]), int(tl["chunk"])
-        assert 0 < ln <= 256 * vec and covered[t] == e0
+        assert 0 < ln <= 256 * vec * iters and covered[t] == e0
         covered[t] += ln
         assert (off[t] + e0) // p.chunk_elems == c == (off[t] + e0 + ln - 1) // p.chunk_elems and c < C
         assert int(tl["start_rank"]) == (c % K if rot else 0)
