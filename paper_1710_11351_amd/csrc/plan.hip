@@ -131,6 +131,12 @@ int device_compute_units() {
     return cached;
 }
 
+// Workgroups of a two-phase launch: two per compute unit (256 VGPRs each), fewer on request.
+int64_t two_phase_grid(const cmn_plan *p) {
+    const int64_t resident = int64_t(2) * device_compute_units();
+    return p->grid_limit > 0 && p->grid_limit < resident ? p->grid_limit : resident;
+}
+
 bool prefer_two_phase(const cmn_plan *p) {
     return !p->one_pass_only && p->K >= 8 && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
 }
@@ -187,6 +193,7 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
     }
     p->tile_elems = kBlock * vec_elems(grad_dtype) * iters;
     if (const char *k = std::getenv("CMN_STEP_KERNEL")) p->one_pass_only = std::strcmp(k, "stream") == 0;
+    if (const char *k = std::getenv("CMN_TWO_PHASE_GRID")) p->grid_limit = std::atoi(k) > 0 ? std::atoi(k) : 0;
     try {
         p->first_tile.assign(size_t(n_tensors) + 1, 0);
     } catch (...) { delete p; return CMN_ENOMEM; }

@@ -43,7 +43,9 @@ struct WorkspaceLayout {
 struct cmn_plan {
     int T = 0, K = 1, C = 1, align_bytes = 256, dtype = CMN_F32, ring_rotate = 1;
     int tile_elems = 0;
-    bool one_pass_only = false;  // CMN_STEP_KERNEL=stream at creation: never pick the two-phase kernels
+    // launch-shape knobs, fixed at creation from the environment (results never depend on them)
+    bool one_pass_only = false;          // CMN_STEP_KERNEL=stream: never pick the two-phase kernels
+    int grid_limit = 0;                  // CMN_TWO_PHASE_GRID: at most this many persistent workgroups (0: 2 per CU)
     std::vector<int64_t> numel;  // [T]
     std::vector<int64_t> off;    // [T+1]
     int64_t N = 0, chunk_elems = 0, L = 0, n_tiles = 0;
@@ -70,6 +72,7 @@ int check_launch(const cmn_plan *p);
 // CMN_STEP_KERNEL=stream in the environment forces the one-pass kernels (A/B runs, tests).
 int device_compute_units();
 bool prefer_two_phase(const cmn_plan *p);
+int64_t two_phase_grid(const cmn_plan *p);
 
 template <typename T>
 inline T *ws_ptr(const cmn_plan *p, size_t byte_off) {

@@ -129,7 +129,7 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
     if (prefer_two_phase(plan) && kReduceIters == 1) {
         // one launch per round of the persistent grid, tiles spread evenly (a kernel boundary
         // realigns the phases of the workgroups)
-        const long long n_tiles = tpc * plan->C, resident = 2LL * device_compute_units();
+        const long long n_tiles = tpc * plan->C, resident = two_phase_grid(plan);
         const long long slots = resident * (kStashFloats / vec_elems(plan->dtype));
         const long long n_launch = (n_tiles + slots - 1) / slots, per_launch = (n_tiles + n_launch - 1) / n_launch;
 #define CMN_LAUNCH_REDUCE2(DT)                                                                                  \

@@ -184,37 +184,42 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int n_tiles) {
     using TV = TileView<DT, SRC_FOLD, MEAN, OPT>;
     constexpr int VEC = TV::VEC;
+    constexpr int Q = VEC / 4;
     constexpr int M = kStashFloats / VEC;
     const int W = gridDim.x;
     for (int tile0 = blockIdx.x; tile0 < n_tiles; tile0 += W * M) {
-        f32x4 gbar[M][VEC / 4];
+        f32x4 gbar[M][Q];
+        auto averaged = [&](int ti, f32x4 (&out)[Q]) {
+            const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+            float gb[VEC];
 #pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const int ti = tile0 + m * W;
-            if (ti < n_tiles) {
-                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+            for (int i = 0; i < VEC; ++i) gb[i] = 0.0f;
+            if (int(threadIdx.x) < tv.nvec)
+                tv.template fold<U>(gb, unsigned(tv.head + threadIdx.x * VEC), scale_ptrs, K, inv_k);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) out[q] = f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]};
+            tv.ragged(scale_ptrs, K, inv_k, o);
+        };
+        auto update = [&](int ti, const f32x4 (&in)[Q]) {
+            const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+            if (int(threadIdx.x) < tv.nvec) {
                 float gb[VEC];
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) gb[i] = 0.0f;
-                if (int(threadIdx.x) < tv.nvec)
-                    tv.template fold<U>(gb, unsigned(tv.head + threadIdx.x * VEC), scale_ptrs, K, inv_k);
-#pragma unroll
-                for (int q = 0; q < VEC / 4; ++q) gbar[m][q] = f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]};
-                tv.ragged(scale_ptrs, K, inv_k, o);
+                for (int i = 0; i < VEC; ++i) gb[i] = in[i / 4][i % 4];
+                tv.template apply<false>(gb, unsigned(tv.head + threadIdx.x * VEC), K, o);
             }
-        }
+        };
+        // phase 1: reads only
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             const int ti = tile0 + m * W;
-            if (ti < n_tiles) {
-                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
-                if (int(threadIdx.x) < tv.nvec) {
-                    float gb[VEC];
+            if (ti < n_tiles) averaged(ti, gbar[m]);
+        }
+        // phase 2: the in-place update burst
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) gb[i] = gbar[m][i / 4][i % 4];
-                    tv.template apply<false>(gb, unsigned(tv.head + threadIdx.x * VEC), K, o);
-                }
-            }
+        for (int m = 0; m < M; ++m) {
+            const int ti = tile0 + m * W;
+            if (ti < n_tiles) update(ti, gbar[m]);
         }
     }
 }
@@ -234,7 +239,7 @@ template <int DT, int MEAN, int OPT>
 inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o,
                                hipStream_t s) {
     constexpr int U = 8;
-    const int64_t resident = int64_t(2) * device_compute_units();   // 2 workgroups per compute unit at 256 VGPRs
+    const int64_t resident = two_phase_grid(p);
     const unsigned grid = unsigned(tile_count < resident ? tile_count : resident);
     hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
                        ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
@@ -266,7 +271,7 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     // kernel boundary realigns the workgroups' phases, which rounds drifting inside one launch
     // would lose (VGG-16, 5.3 rounds: 1931 us in one launch, 1830 us in six).  The tiles are
     // spread evenly over the launches.
-    const int64_t slots = int64_t(2) * device_compute_units() * (kStashFloats / vec_elems(plan->dtype));
+    const int64_t slots = two_phase_grid(plan) * (kStashFloats / vec_elems(plan->dtype));
     const int64_t n_launch = (n + slots - 1) / slots, per_launch = (n + n_launch - 1) / n_launch;
 #define CMN_STEP_CASE(DT, MEAN)                                                                          \
     do {                                                                                                 \

@@ -50,6 +50,18 @@ def test_launch_shape_knobs_do_not_change_results(monkeypatch, env, dtype):
     run_parity(c, steps=1, staged=True, fused=False)
 
 
+@pytest.mark.parametrize("dtype,opt", [("f32", "sgd"), ("f16", "sgd"), ("f32", "adam"), ("bf16", "adam")])
+def test_two_phase_rounds_at_small_size(monkeypatch, dtype, opt):
+    """Three persistent workgroups instead of two per compute unit: the list no longer fits one
+    round of the register stash, so the one-launch-per-round split (fused step and ring reduce)
+    is exercised at a size the oracle finishes quickly."""
+    monkeypatch.setenv("CMN_TWO_PHASE_GRID", "3")
+    numel = [200_000, 5, 0, 150_001, 64, 70_000, 7, 2049]
+    c = wl.custom_config(numel, K=8, n_chunks=5, grad_dtype=dtype, cfg=75, wd=1e-3)
+    run_parity(c, steps=2, misalign=0, opt=opt)
+    run_parity(c, steps=1, misalign=1, opt=opt, staged=False)
+
+
 def test_single_replica_is_the_plain_optimizer():
     c = wl.custom_config([3000, 100], K=1, n_chunks=1, cfg=93)
     run_parity(c, steps=2)
