@@ -114,31 +114,33 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(void *base, unsigned
     return __builtin_amdgcn_make_buffer_rsrc(base, 0, int(bytes), 0x00020000 /* 32-bit data format */);
 }
 
-// 16-byte store at byte_off that is written through L2 towards memory at once
-// (cache-policy bit sc1, aux value 16) instead of lingering as a dirty line until
-// evicted.  On MI355X the write traffic of a read-dominated kernel is cheaper this way
-// (measured: about 2 % of the fused step's time); the data written is the same.
-__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f32x4 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
-}
-// The same store with the default (write-back) policy.
-__device__ __forceinline__ void store_back(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f32x4 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 0);
-}
-template <bool WT>
-__device__ __forceinline__ void store_out(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f32x4 v) {
-    if (WT) store_through(r, byte_off, v); else store_back(r, byte_off, v);
+// 16-byte store at byte_off with an explicit cache policy (the auxiliary operand of the
+// buffer store: bit 1 = nt, bit 4 = sc1).  The data written is the same under every policy;
+// which one is cheapest depends on what else the kernel has in flight, so each store site
+// names its policy.
+//   ST_BACK     default write-back: the line lingers dirty in L2 until evicted
+//   ST_THROUGH  sc1: written through towards memory at once
+//   ST_STREAM   nt: streaming data nobody re-reads soon
+enum { ST_BACK = 0, ST_STREAM = 2, ST_THROUGH = 16, ST_STREAM_THROUGH = 18 };
+template <int POLICY, class V>
+__device__ __forceinline__ void store_vec(__amdgpu_buffer_rsrc_t r, unsigned byte_off, V v) {
+    static_assert(sizeof(V) == 16, "one 16-byte vector");
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, POLICY);
 }
 
-__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, f16x8 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
-}
-__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, u16x8 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
-}
-__device__ __forceinline__ void store_through(__amdgpu_buffer_rsrc_t r, unsigned byte_off, i8x16 v) {
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v, v), r, int(byte_off), 0, 16);
-}
+// Per-site policies, each chosen by A/B measurement on MI355X (ResNet-50 list):
+//  - p and optimizer state are read again by the next step and fit the memory-side cache:
+//    streaming them out (nt) costs the one-pass kernel 17 % at K = 4.  One-pass kernels write
+//    them through (2 % better than write-back while reads are in flight); the write phase of
+//    the two-phase kernel is a pure burst and does best with plain write-back.
+//  - the averaged gradient handed to the mean tensors or back to the K replicas is not read
+//    again by this library: nt + sc1 (K = 32: 586 -> 557 us with the mean stored, 1258 -> 1089 us
+//    with all replicas overwritten; K = 4: 228 -> 174 us).
+constexpr int kStoreStateOnePass = ST_THROUGH;
+constexpr int kStoreStatePhase2 = ST_BACK;
+constexpr int kStoreAverage = ST_STREAM_THROUGH;
+constexpr int kStoreReducedOnePass = ST_THROUGH;   // ring reduce, one-pass
+constexpr int kStoreReducedPhase2 = ST_BACK;       // ring reduce, two-phase (scale+unpack reads it next; nt: no gain)
 
 // The K-term sum starts from -0.0f because x + (-0.0f) == x for every x, signed
 // zeros included, so the first addition reproduces the first gradient exactly.

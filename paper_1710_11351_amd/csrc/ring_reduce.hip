@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
             f32x4 o;
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[i] = acc[4 * q + i];
-            store_through(out, unsigned(e + 4 * q) * 4u, o);
+            store_vec<kStoreReducedOnePass>(out, unsigned(e + 4 * q) * 4u, o);
         }
     }
 }
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
                 const __amdgpu_buffer_rsrc_t out = make_rsrc(dst, unsigned(in_chunk) * 4u);
                 if (e < in_chunk) {
 #pragma unroll
-                    for (int q = 0; q < VEC / 4; ++q) store_back(out, unsigned(e + 4 * q) * 4u, stash[m][q]);
+                    for (int q = 0; q < VEC / 4; ++q) store_vec<kStoreReducedPhase2>(out, unsigned(e + 4 * q) * 4u, stash[m][q]);
                 }
             }
         }

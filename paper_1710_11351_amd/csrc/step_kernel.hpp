@@ -69,9 +69,9 @@ struct TileView {
         for (int i = 0; i < G::VEC; ++i) gb[i] = gb[i] * inv_k;
     }
 
-    // optimizer on the vector at element e, parameter and state fetched here, results (and the
-    // averaged gradient, where asked for) stored write-through
-    template <bool WT = true>
+    // optimizer on the vector at element e, parameter and state fetched here; results (and the
+    // averaged gradient, where asked for) stored with the policy of the calling kernel's kind
+    template <bool ONE_PASS = true>
     __device__ __forceinline__ void apply(const float (&gb)[VEC], unsigned e, int K, const OptArgs &o) const {
         const unsigned bytes = unsigned(len) * 4u;
         const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, bytes);
@@ -95,17 +95,17 @@ struct TileView {
                 if (ADAM) s2v[q][i] = b;
             }
             if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS)
-                store_out<WT>(m_out, (e + 4 * q) * 4u, f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]});
-            if (ADAM) store_out<WT>(s2_out, (e + 4 * q) * 4u, s2v[q]);
-            store_out<WT>(s1_out, (e + 4 * q) * 4u, s1v[q]);
-            store_out<WT>(p_out, (e + 4 * q) * 4u, pv[q]);
+                store_vec<kStoreAverage>(m_out, (e + 4 * q) * 4u, f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]});
+            if (ADAM) store_vec<ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2>(s2_out, (e + 4 * q) * 4u, s2v[q]);
+            store_vec<ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2>(s1_out, (e + 4 * q) * 4u, s1v[q]);
+            store_vec<ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2>(p_out, (e + 4 * q) * 4u, pv[q]);
         }
         if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
             // every gradient of this vector has been read before; hand the average to each replica
             const typename G::raw avg = G::encode_vec(gb);
             for (int k = 0; k < K; ++k) {
                 elem *dst = static_cast<elem *>(const_cast<void *>(gcol[k])) + e0;
-                store_through(make_rsrc(dst, unsigned(len) * unsigned(sizeof(elem))), e * unsigned(sizeof(elem)), avg);
+                store_vec<kStoreAverage>(make_rsrc(dst, unsigned(len) * unsigned(sizeof(elem))), e * unsigned(sizeof(elem)), avg);
             }
         }
     }
