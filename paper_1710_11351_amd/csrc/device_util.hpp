@@ -9,6 +9,7 @@
 #include <cstdint>
 
 #include "../../include/cmn.h"
+#include "plan.hpp"
 
 #pragma clang fp contract(off)
 
@@ -141,6 +142,43 @@ constexpr int kStoreStatePhase2 = ST_BACK;
 constexpr int kStoreAverage = ST_STREAM_THROUGH;
 constexpr int kStoreReducedOnePass = ST_THROUGH;   // ring reduce, one-pass
 constexpr int kStoreReducedPhase2 = ST_BACK;       // ring reduce, two-phase (scale+unpack reads it next; nt: no gain)
+
+// Re-dealing the floats of a wavefront so that fp32 accesses coalesce.  A thread that loads one
+// 16-byte vector of a narrow type owns 4Q consecutive elements (Q = 2 for 16-bit, 4 for int8
+// gradients), so its Q float4s lie 16Q bytes from the next lane's and every fp32 load or store
+// instruction would touch only half or a quarter of each cache line (measured: the int8 ring
+// reduce at K = 4 takes 88 us that way and 33 us dealt).  A wavefront's 64 runs form one block
+// of 256Q consecutive floats.
+//   run order:   v[q] = floats [4q, 4q + 4) of lane l's run, which starts at float 4Q*l
+//   dealt order: v[q] = floats [256q + 4l, 256q + 4l + 4) of the block: instruction q covers 1 KB
+// buf holds kBlock * Q float4s of LDS; each wavefront uses its own part, so the exchange needs
+// no workgroup barrier.  Every lane of the wavefront must call these (inactive ones pass zeros).
+template <int Q>
+__device__ __forceinline__ void wave_exchange(f32x4 (&v)[Q], f32x4 *buf, bool to_dealt) {
+    if constexpr (Q > 1) {
+        const int lane = threadIdx.x & 63;
+        f32x4 *w = buf + (threadIdx.x >> 6) * 64 * Q;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) w[to_dealt ? lane * Q + q : q * 64 + lane] = v[q];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int q = 0; q < Q; ++q) v[q] = w[to_dealt ? q * 64 + lane : lane * Q + q];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the next exchange must not overtake these reads
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+template <int Q> __device__ __forceinline__ void wave_deal(f32x4 (&v)[Q], f32x4 *buf) { wave_exchange<Q>(v, buf, true); }
+template <int Q> __device__ __forceinline__ void wave_undeal(f32x4 (&v)[Q], f32x4 *buf) { wave_exchange<Q>(v, buf, false); }
+
+// Float offset, inside the 256Q * 4 floats the workgroup's 256 runs cover, of this thread's
+// q-th float4 in dealt order.  For Q = 1 it is the thread's own run: 4 * threadIdx.x.
+template <int Q>
+__device__ __forceinline__ unsigned dealt_offset(int q) {
+    return (threadIdx.x >> 6) * 256u * Q + unsigned(q) * 256u + (threadIdx.x & 63) * 4u;
+}
+template <int Q> constexpr int deal_buffer_vectors() { return Q > 1 ? kBlock * Q : 1; }
 
 // The K-term sum starts from -0.0f because x + (-0.0f) == x for every x, signed
 // zeros included, so the first addition reproduces the first gradient exactly.

@@ -37,21 +37,23 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
     const __amdgpu_buffer_rsrc_t out = make_rsrc(dst, unsigned(in_chunk) * 4u);
 
     // chunk_elems is a multiple of the alignment, hence of VEC: no ragged vectors
-    for (int e = threadIdx.x * VEC; e < in_chunk; e += kBlock * VEC) {
-        float acc[VEC];
+    constexpr int Q = VEC / 4;
+    __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
+    const int e = threadIdx.x * VEC;
+    float acc[VEC];
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
+    for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
+    if (e < in_chunk)
         fold_all<DT, U>(
             acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
             [&](int j) { return scale_ptrs[ring_rank(s, j, K)][c]; });
+    f32x4 o[Q];
 #pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            f32x4 o;
+    for (int q = 0; q < Q; ++q) o[q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+    wave_deal<Q>(o, deal_buf);                       // fp32 stores that cover whole cache lines
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = acc[4 * q + i];
-            store_vec<kStoreReducedOnePass>(out, unsigned(e + 4 * q) * 4u, o);
-        }
-    }
+    for (int q = 0; q < Q; ++q)                      // past in_chunk the buffer bounds drop the store
+        store_vec<kStoreReducedOnePass>(out, dealt_offset<Q>(q) * 4u, o[q]);
 }
 
 template <int DT, int U>
@@ -63,6 +65,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
     constexpr int VEC = G::VEC;
     constexpr int TILE = kBlock * VEC;
     constexpr int M = kStashFloats / VEC;
+    constexpr int Q = VEC / 4;
+    __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
     const int W = gridDim.x;
     const int e = threadIdx.x * VEC;
     // this launch owns the (chunk, tile) pairs numbered [tile_begin, n_tiles)
@@ -84,7 +88,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
                         acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
                         [&](int j) { return scale_ptrs[ring_rank(s, j, K)][c]; });
 #pragma unroll
-                for (int q = 0; q < VEC / 4; ++q) stash[m][q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+                for (int q = 0; q < Q; ++q) stash[m][q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+                wave_deal<Q>(stash[m], deal_buf);
             }
         }
 #pragma unroll
@@ -95,10 +100,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
                 const int in_chunk = int(min((long long)TILE, chunk_elems - (long long)tile * TILE));
                 float *dst = reduced + c * chunk_elems + (long long)tile * TILE;
                 const __amdgpu_buffer_rsrc_t out = make_rsrc(dst, unsigned(in_chunk) * 4u);
-                if (e < in_chunk) {
 #pragma unroll
-                    for (int q = 0; q < VEC / 4; ++q) store_vec<kStoreReducedPhase2>(out, unsigned(e + 4 * q) * 4u, stash[m][q]);
-                }
+                for (int q = 0; q < Q; ++q)              // past in_chunk the buffer bounds drop the store
+                    store_vec<kStoreReducedPhase2>(out, dealt_offset<Q>(q) * 4u, stash[m][q]);
             }
         }
     }

@@ -33,6 +33,7 @@ struct TileView {
     using G = GradT<DT>;
     using elem = typename G::elem;
     static constexpr int VEC = SRC == SRC_MEAN ? 4 : G::VEC;
+    static constexpr int Q = VEC / 4;   // float4s per thread and tile
     static constexpr bool ADAM = OPT == OPT_ADAM;
     static constexpr bool USE_MEAN_TENSOR = SRC == SRC_MEAN || MEAN == CMN_MEAN_TO_MEAN_GRADS;
 
@@ -56,56 +57,94 @@ struct TileView {
         tail0 = head + nvec * VEC;
     }
 
-    // averaged gradient of the 16-byte vector at element e: fold of the K replicas, times 1/K
+    // Averaged gradient of the thread's run of VEC elements (vector number vi of the tile): fold of
+    // the K replicas, times 1/K, then dealt over the wavefront so that the fp32 side coalesces.
+    // Every thread of the workgroup calls this; a thread without a vector contributes zeros.
     template <int U>
-    __device__ __forceinline__ void fold(float (&gb)[G::VEC], unsigned e, const float *const *scale_ptrs, int K,
-                                         float inv_k) const {
+    __device__ __forceinline__ void averaged(f32x4 (&out)[Q], int vi, const float *const *scale_ptrs, int K,
+                                             float inv_k, f32x4 *deal_buf) const {
+        float gb[VEC];
 #pragma unroll
-        for (int i = 0; i < G::VEC; ++i) gb[i] = sum_identity();
-        fold_all<DT, U>(
-            gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + e0 + e; },
-            [&](int j) { return scale_ptrs[ring_rank(s, j, K)][chunk]; });
+        for (int i = 0; i < VEC; ++i) gb[i] = 0.0f;
+        if (vi < nvec) {
+            const unsigned e = unsigned(head + vi * VEC);
 #pragma unroll
-        for (int i = 0; i < G::VEC; ++i) gb[i] = gb[i] * inv_k;
+            for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
+            fold_all<DT, U>(
+                gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + e0 + e; },
+                [&](int j) { return scale_ptrs[ring_rank(s, j, K)][chunk]; });
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
+        }
+#pragma unroll
+        for (int q = 0; q < Q; ++q) out[q] = f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]};
+        wave_deal<Q>(out, deal_buf);
     }
 
-    // optimizer on the vector at element e, parameter and state fetched here; results (and the
-    // averaged gradient, where asked for) stored with the policy of the calling kernel's kind
+    // The same from the bound mean-gradient tensor (optimizer-only kernels, Q = 1).
+    __device__ __forceinline__ void averaged_from_mean(f32x4 (&out)[Q], int vi) const {
+        static_assert(SRC != SRC_MEAN || Q == 1, "the mean gradient is fp32");
+        out[0] = vi < nvec ? load_vec<f32x4>(m + head + vi * 4) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+
+    // Optimizer on the thread's Q float4s in dealt order (g from averaged() of the same round,
+    // vi0 = number of the round's first vector): parameter and state fetched here; results, and
+    // the averaged gradient where asked for, stored with the policy of the calling kernel's kind.
     template <bool ONE_PASS = true>
-    __device__ __forceinline__ void apply(const float (&gb)[VEC], unsigned e, int K, const OptArgs &o) const {
+    __device__ __forceinline__ void apply(const f32x4 (&g)[Q], int vi0, int K, const OptArgs &o, f32x4 *deal_buf) const {
         const unsigned bytes = unsigned(len) * 4u;
         const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, bytes);
         const __amdgpu_buffer_rsrc_t s1_out = make_rsrc(s1, bytes);
         const __amdgpu_buffer_rsrc_t s2_out = make_rsrc(s2, ADAM ? bytes : 0u);
         const __amdgpu_buffer_rsrc_t m_out = make_rsrc(m, MEAN == CMN_MEAN_TO_MEAN_GRADS ? bytes : 0u);
-        f32x4 pv[VEC / 4], s1v[VEC / 4], s2v[VEC / 4];
+        constexpr int ST = ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2;
+        const unsigned end = unsigned(nvec) * VEC;             // floats of the tile covered by whole vectors
+        unsigned x[Q];
+        f32x4 pv[Q], s1v[Q], s2v[Q];
 #pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            pv[q] = load_vec<f32x4>(p + e + 4 * q);
-            s1v[q] = load_vec<f32x4>(s1 + e + 4 * q);
-            if (ADAM) s2v[q] = load_vec<f32x4>(s2 + e + 4 * q);
-        }
-#pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float pi = pv[q][i], a = s1v[q][i], b = ADAM ? s2v[q][i] : 0.0f;
-                opt_update<OPT>(gb[4 * q + i], pi, a, b, o);
-                pv[q][i] = pi; s1v[q][i] = a;
-                if (ADAM) s2v[q][i] = b;
+        for (int q = 0; q < Q; ++q) {
+            x[q] = unsigned(vi0) * VEC + dealt_offset<Q>(q);   // multiple of 4, like end
+            if (x[q] < end) {
+                pv[q] = load_vec<f32x4>(p + head + x[q]);
+                s1v[q] = load_vec<f32x4>(s1 + head + x[q]);
+                if (ADAM) s2v[q] = load_vec<f32x4>(s2 + head + x[q]);
             }
-            if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS)
-                store_vec<kStoreAverage>(m_out, (e + 4 * q) * 4u, f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]});
-            if (ADAM) store_vec<ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2>(s2_out, (e + 4 * q) * 4u, s2v[q]);
-            store_vec<ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2>(s1_out, (e + 4 * q) * 4u, s1v[q]);
-            store_vec<ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2>(p_out, (e + 4 * q) * 4u, pv[q]);
         }
-        if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
-            // every gradient of this vector has been read before; hand the average to each replica
-            const typename G::raw avg = G::encode_vec(gb);
-            for (int k = 0; k < K; ++k) {
-                elem *dst = static_cast<elem *>(const_cast<void *>(gcol[k])) + e0;
-                store_vec<kStoreAverage>(make_rsrc(dst, unsigned(len) * unsigned(sizeof(elem))), e * unsigned(sizeof(elem)), avg);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            if (x[q] < end) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float pi = pv[q][i], a = s1v[q][i], b = ADAM ? s2v[q][i] : 0.0f;
+                    opt_update<OPT>(g[q][i], pi, a, b, o);
+                    pv[q][i] = pi; s1v[q][i] = a;
+                    if (ADAM) s2v[q][i] = b;
+                }
+                const unsigned off = (unsigned(head) + x[q]) * 4u;
+                if (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_MEAN_GRADS) store_vec<kStoreAverage>(m_out, off, g[q]);
+                if (ADAM) store_vec<ST>(s2_out, off, s2v[q]);
+                store_vec<ST>(s1_out, off, s1v[q]);
+                store_vec<ST>(p_out, off, pv[q]);
+            }
+        }
+        if constexpr (SRC == SRC_FOLD && MEAN == CMN_MEAN_TO_ALL_REPLICAS) {
+            // every gradient of these vectors has been read before; hand the average to each replica,
+            // encoded from run order (one 16-byte vector per thread again)
+            f32x4 r[Q];
+#pragma unroll
+            for (int q = 0; q < Q; ++q) r[q] = g[q];
+            wave_undeal<Q>(r, deal_buf);
+            const int vi = vi0 + int(threadIdx.x);
+            if (vi < nvec) {
+                float gb[VEC];
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) gb[i] = r[i / 4][i % 4];
+                const typename G::raw avg = G::encode_vec(gb);
+                const unsigned e = unsigned(head + vi * VEC);
+                for (int k = 0; k < K; ++k) {
+                    elem *dst = static_cast<elem *>(const_cast<void *>(gcol[k])) + e0;
+                    store_vec<kStoreAverage>(make_rsrc(dst, unsigned(len) * unsigned(sizeof(elem))), e * unsigned(sizeof(elem)), avg);
+                }
             }
         }
     }
@@ -151,19 +190,14 @@ __global__ __launch_bounds__(kBlock) void k_step(
     float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
     const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
     using TV = TileView<DT, SRC, MEAN, OPT>;
-    constexpr int VEC = TV::VEC;
+    constexpr int Q = TV::Q;
+    __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
     const TV tv(tiles[blockIdx.x], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
-    for (int vi = threadIdx.x; vi < tv.nvec; vi += kBlock) {
-        const unsigned e = unsigned(tv.head + vi * VEC);
-        float gb[VEC];
-        if constexpr (SRC == SRC_MEAN) {
-            const f32x4 g = load_vec<f32x4>(tv.m + e);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) gb[i] = g[i];
-        } else {
-            tv.template fold<U>(gb, e, scale_ptrs, K, inv_k);
-        }
-        tv.apply(gb, e, K, o);
+    for (int vi0 = 0; vi0 < tv.nvec; vi0 += kBlock) {          // same trip count for the whole workgroup
+        f32x4 g[Q];
+        if constexpr (SRC == SRC_MEAN) tv.averaged_from_mean(g, vi0 + int(threadIdx.x));
+        else tv.template averaged<U>(g, vi0 + int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
+        tv.apply(g, vi0, K, o, deal_buf);
     }
     tv.ragged(scale_ptrs, K, inv_k, o);
 }
@@ -183,43 +217,28 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
     const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int n_tiles) {
     using TV = TileView<DT, SRC_FOLD, MEAN, OPT>;
-    constexpr int VEC = TV::VEC;
-    constexpr int Q = VEC / 4;
-    constexpr int M = kStashFloats / VEC;
+    constexpr int Q = TV::Q;
+    constexpr int M = kStashFloats / TV::VEC;
+    __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
     const int W = gridDim.x;
     for (int tile0 = blockIdx.x; tile0 < n_tiles; tile0 += W * M) {
-        f32x4 gbar[M][Q];
-        auto averaged = [&](int ti, f32x4 (&out)[Q]) {
-            const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
-            float gb[VEC];
+        f32x4 gbar[M][Q];                                      // dealt order
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) gb[i] = 0.0f;
-            if (int(threadIdx.x) < tv.nvec)
-                tv.template fold<U>(gb, unsigned(tv.head + threadIdx.x * VEC), scale_ptrs, K, inv_k);
-#pragma unroll
-            for (int q = 0; q < Q; ++q) out[q] = f32x4{gb[4 * q], gb[4 * q + 1], gb[4 * q + 2], gb[4 * q + 3]};
-            tv.ragged(scale_ptrs, K, inv_k, o);
-        };
-        auto update = [&](int ti, const f32x4 (&in)[Q]) {
-            const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
-            if (int(threadIdx.x) < tv.nvec) {
-                float gb[VEC];
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) gb[i] = in[i / 4][i % 4];
-                tv.template apply<false>(gb, unsigned(tv.head + threadIdx.x * VEC), K, o);
+        for (int m = 0; m < M; ++m) {
+            const int ti = tile0 + m * W;
+            if (ti < n_tiles) {
+                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                tv.template averaged<U>(gbar[m], int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
+                tv.ragged(scale_ptrs, K, inv_k, o);
             }
-        };
-        // phase 1: reads only
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const int ti = tile0 + m * W;
-            if (ti < n_tiles) averaged(ti, gbar[m]);
         }
-        // phase 2: the in-place update burst
 #pragma unroll
         for (int m = 0; m < M; ++m) {
             const int ti = tile0 + m * W;
-            if (ti < n_tiles) update(ti, gbar[m]);
+            if (ti < n_tiles) {
+                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                tv.template apply<false>(gbar[m], 0, K, o, deal_buf);
+            }
         }
     }
 }
