@@ -27,6 +27,24 @@ __device__ __forceinline__ constexpr int head_index() {
                              : (MEAN == CMN_MEAN_TO_MEAN_GRADS ? CMN_HEAD_STEP_MEAN : CMN_HEAD_STEP);
 }
 
+// A table entry as the eight 32-bit words it occupies: read as words it travels through one
+// scalar load (a byte-sized field on its own would need a vector load and a broadcast).
+struct TileWords {
+    uint32_t w[8];
+    __device__ __forceinline__ long long e0() const { return (long long)(((unsigned long long)w[1] << 32) | w[0]); }
+    __device__ __forceinline__ int len() const { return int(w[2]); }
+    __device__ __forceinline__ int tensor() const { return int(w[3]); }
+    __device__ __forceinline__ int start_rank() const { return int(w[4]); }
+    __device__ __forceinline__ int chunk() const { return int(w[5]); }
+    __device__ __forceinline__ int head(int i) const { return int(int8_t((w[6 + i / 4] >> (8 * (i % 4))) & 0xffu)); }
+};
+static_assert(sizeof(cmn_tile) == sizeof(TileWords) && offsetof(cmn_tile, len) == 8 && offsetof(cmn_tile, tensor) == 12 &&
+                  offsetof(cmn_tile, start_rank) == 16 && offsetof(cmn_tile, chunk) == 20 && offsetof(cmn_tile, head) == 24,
+              "TileWords mirrors cmn_tile");
+__device__ __forceinline__ TileWords load_tile(const cmn_tile *tiles, int i) {
+    return *reinterpret_cast<const TileWords *>(tiles + i);
+}
+
 // Everything a kernel needs to know about one tile, derived from its table entry.
 template <int DT, int SRC, int MEAN, int OPT>
 struct TileView {
@@ -42,16 +60,16 @@ struct TileView {
     const void *const *gcol;
     float *p, *s1, *s2, *m;
 
-    __device__ __forceinline__ TileView(const cmn_tile &tl, const void *const *grad_cols, float *const *param_ptrs,
+    __device__ __forceinline__ TileView(const TileWords &tl, const void *const *grad_cols, float *const *param_ptrs,
                                         float *const *s1_ptrs, float *const *s2_ptrs, float *const *mean_ptrs, int K) {
-        const int t = tl.tensor;
-        e0 = tl.e0; len = tl.len; s = tl.start_rank; chunk = tl.chunk;
+        const int t = tl.tensor();
+        e0 = tl.e0(); len = tl.len(); s = tl.start_rank(); chunk = tl.chunk();
         gcol = grad_cols + size_t(t) * size_t(K);
         p = param_ptrs[t] + e0;
         s1 = s1_ptrs[t] + e0;
         s2 = ADAM ? s2_ptrs[t] + e0 : nullptr;
         m = USE_MEAN_TENSOR ? mean_ptrs[t] + e0 : nullptr;
-        head = tl.head[head_index<SRC, MEAN, OPT>()];
+        head = tl.head(head_index<SRC, MEAN, OPT>());
         if (head < 0 || head > len) head = len;
         nvec = (len - head) / VEC;
         tail0 = head + nvec * VEC;
@@ -192,7 +210,7 @@ __global__ __launch_bounds__(kBlock) void k_step(
     using TV = TileView<DT, SRC, MEAN, OPT>;
     constexpr int Q = TV::Q;
     __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
-    const TV tv(tiles[blockIdx.x], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+    const TV tv(load_tile(tiles, blockIdx.x), grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
     for (int vi0 = 0; vi0 < tv.nvec; vi0 += kBlock) {          // same trip count for the whole workgroup
         f32x4 g[Q];
         if constexpr (SRC == SRC_MEAN) tv.averaged_from_mean(g, vi0 + int(threadIdx.x));
@@ -227,7 +245,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
         for (int m = 0; m < M; ++m) {
             const int ti = tile0 + m * W;
             if (ti < n_tiles) {
-                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                const TV tv(load_tile(tiles, ti), grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
                 tv.template averaged<U>(gbar[m], int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
                 tv.ragged(scale_ptrs, K, inv_k, o);
             }
@@ -236,7 +254,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
         for (int m = 0; m < M; ++m) {
             const int ti = tile0 + m * W;
             if (ti < n_tiles) {
-                const TV tv(tiles[ti], grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                const TV tv(load_tile(tiles, ti), grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
                 tv.template apply<false>(gbar[m], 0, K, o, deal_buf);
             }
         }
