@@ -24,7 +24,7 @@ static WorkspaceLayout make_layout(int T, int K, int64_t n_tiles) {
     w.mean_ptrs = o;  o = round256(o + sizeof(void *) * size_t(T));
     w.state2_ptrs = o; o = round256(o + sizeof(void *) * size_t(T));
     w.scale_ptrs = o;  o = round256(o + sizeof(void *) * size_t(K));
-    w.tiles = o;      o = round256(o + sizeof(cmn_tile) * size_t(n_tiles));
+    w.tiles = o;      o = round256(o + sizeof(DeviceTile) * size_t(n_tiles));
     w.total = o < 256 ? 256 : o;
     return w;
 }
@@ -257,9 +257,21 @@ static int upload_image(cmn_plan *p, void *dev_workspace, hipStream_t s) {
             flat.assign(reinterpret_cast<const void *const *>(img + p->ws.grad_rows),
                         reinterpret_cast<const void *const *>(img + p->ws.grad_rows) + size_t(p->K) * p->T);
         }
-        build_tiles(*p, p->have_grads ? flat.data() : nullptr, p->have_opt ? tab(p->ws.param_ptrs) : nullptr,
-                    p->have_opt ? tab(p->ws.vel_ptrs) : nullptr, p->have_mean ? tab(p->ws.mean_ptrs) : nullptr,
-                    p->have_state2 ? tab(p->ws.state2_ptrs) : nullptr, reinterpret_cast<cmn_tile *>(img + p->ws.tiles));
+        void *const *pp = p->have_opt ? tab(p->ws.param_ptrs) : nullptr, *const *vp = p->have_opt ? tab(p->ws.vel_ptrs) : nullptr;
+        void *const *mp = p->have_mean ? tab(p->ws.mean_ptrs) : nullptr, *const *sp = p->have_state2 ? tab(p->ws.state2_ptrs) : nullptr;
+        std::vector<cmn_tile> table(size_t(p->n_tiles));
+        build_tiles(*p, p->have_grads ? flat.data() : nullptr, pp, vp, mp, sp, table.data());
+        DeviceTile *out = reinterpret_cast<DeviceTile *>(img + p->ws.tiles);
+        auto at = [](void *const *base, const cmn_tile &tl) {
+            return base ? static_cast<float *>(base[tl.tensor]) + tl.e0 : nullptr;
+        };
+        for (size_t i = 0; i < table.size(); ++i) {
+            const cmn_tile &tl = table[i];
+            DeviceTile &d = out[i];
+            d.p = at(pp, tl); d.s1 = at(vp, tl); d.s2 = at(sp, tl); d.m = at(mp, tl);
+            d.e0 = tl.e0; d.len = tl.len; d.tensor = tl.tensor; d.start_rank = tl.start_rank; d.chunk = tl.chunk;
+            std::memcpy(d.head, tl.head, sizeof d.head);
+        }
     } catch (...) { return CMN_ENOMEM; }
     if (hipMemcpyAsync(dev_workspace, img, p->ws.total, hipMemcpyHostToDevice, s) != hipSuccess) return CMN_EHIP;
     if (hipStreamSynchronize(s) != hipSuccess) return CMN_EHIP;

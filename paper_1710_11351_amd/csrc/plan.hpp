@@ -21,6 +21,19 @@ constexpr int kTileIters = 1;
 // write phase (leaves ~50 of the 256 registers available at two waves per SIMD for the fold).
 constexpr int kStashFloats = 200;
 
+// What the tensor-space kernels read per tile: the fields of the public cmn_tile plus the tile's
+// own addresses, so that one 64-byte scalar load yields everything but the gradient pointers
+// (looking p, state and mean gradient up by tensor index would put three more dependent scalar
+// loads in front of every tile's first vector load).
+struct DeviceTile {
+    float *p, *s1, *s2, *m;   // parameter, optimizer state (velocity or first moment), Adam's second moment,
+                              // mean gradient, each at element e0 of the tensor; null where not bound
+    int64_t e0;
+    int32_t len, tensor, start_rank, chunk;
+    int8_t head[8];
+};
+static_assert(sizeof(DeviceTile) == 64, "one scalar cache line");
+
 inline int elem_bytes(int dtype) { return dtype == CMN_F32 ? 4 : dtype == CMN_I8S ? 1 : 2; }
 inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }
 
@@ -34,7 +47,7 @@ struct WorkspaceLayout {
     size_t mean_ptrs = 0;    // float* [T]
     size_t state2_ptrs = 0;  // float* [T]   Adam second moments
     size_t scale_ptrs = 0;   // float* [K]   per-replica arrays of n_chunks scales (int8 gradients)
-    size_t tiles = 0;        // cmn_tile [n_tiles]
+    size_t tiles = 0;        // DeviceTile [n_tiles]        // cmn_tile [n_tiles]
     size_t total = 0;
 };
 

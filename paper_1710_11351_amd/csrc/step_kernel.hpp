@@ -27,21 +27,31 @@ __device__ __forceinline__ constexpr int head_index() {
                              : (MEAN == CMN_MEAN_TO_MEAN_GRADS ? CMN_HEAD_STEP_MEAN : CMN_HEAD_STEP);
 }
 
-// A table entry as the eight 32-bit words it occupies: read as words it travels through one
+// A table entry as the sixteen 32-bit words it occupies: read as words it travels through one
 // scalar load (a byte-sized field on its own would need a vector load and a broadcast).
 struct TileWords {
-    uint32_t w[8];
-    __device__ __forceinline__ long long e0() const { return (long long)(((unsigned long long)w[1] << 32) | w[0]); }
-    __device__ __forceinline__ int len() const { return int(w[2]); }
-    __device__ __forceinline__ int tensor() const { return int(w[3]); }
-    __device__ __forceinline__ int start_rank() const { return int(w[4]); }
-    __device__ __forceinline__ int chunk() const { return int(w[5]); }
-    __device__ __forceinline__ int head(int i) const { return int(int8_t((w[6 + i / 4] >> (8 * (i % 4))) & 0xffu)); }
+    uint32_t w[16];
+    template <typename T> __device__ __forceinline__ T *ptr(int i) const {
+        return reinterpret_cast<T *>((unsigned long long)w[2 * i + 1] << 32 | w[2 * i]);
+    }
+    __device__ __forceinline__ float *p() const { return ptr<float>(0); }
+    __device__ __forceinline__ float *s1() const { return ptr<float>(1); }
+    __device__ __forceinline__ float *s2() const { return ptr<float>(2); }
+    __device__ __forceinline__ float *m() const { return ptr<float>(3); }
+    __device__ __forceinline__ long long e0() const { return (long long)(((unsigned long long)w[9] << 32) | w[8]); }
+    __device__ __forceinline__ int len() const { return int(w[10]); }
+    __device__ __forceinline__ int tensor() const { return int(w[11]); }
+    __device__ __forceinline__ int start_rank() const { return int(w[12]); }
+    __device__ __forceinline__ int chunk() const { return int(w[13]); }
+    __device__ __forceinline__ int head(int i) const { return int(int8_t((w[14 + i / 4] >> (8 * (i % 4))) & 0xffu)); }
 };
-static_assert(sizeof(cmn_tile) == sizeof(TileWords) && offsetof(cmn_tile, len) == 8 && offsetof(cmn_tile, tensor) == 12 &&
-                  offsetof(cmn_tile, start_rank) == 16 && offsetof(cmn_tile, chunk) == 20 && offsetof(cmn_tile, head) == 24,
-              "TileWords mirrors cmn_tile");
-__device__ __forceinline__ TileWords load_tile(const cmn_tile *tiles, int i) {
+static_assert(sizeof(DeviceTile) == sizeof(TileWords) && offsetof(DeviceTile, p) == 0 && offsetof(DeviceTile, s1) == 8 &&
+                  offsetof(DeviceTile, s2) == 16 && offsetof(DeviceTile, m) == 24 && offsetof(DeviceTile, e0) == 32 &&
+                  offsetof(DeviceTile, len) == 40 && offsetof(DeviceTile, tensor) == 44 &&
+                  offsetof(DeviceTile, start_rank) == 48 && offsetof(DeviceTile, chunk) == 52 &&
+                  offsetof(DeviceTile, head) == 56,
+              "TileWords mirrors DeviceTile");
+__device__ __forceinline__ TileWords load_tile(const DeviceTile *tiles, int i) {
     return *reinterpret_cast<const TileWords *>(tiles + i);
 }
 
@@ -60,15 +70,13 @@ struct TileView {
     const void *const *gcol;
     float *p, *s1, *s2, *m;
 
-    __device__ __forceinline__ TileView(const TileWords &tl, const void *const *grad_cols, float *const *param_ptrs,
-                                        float *const *s1_ptrs, float *const *s2_ptrs, float *const *mean_ptrs, int K) {
-        const int t = tl.tensor();
+    __device__ __forceinline__ TileView(const TileWords &tl, const void *const *grad_cols, int K) {
         e0 = tl.e0(); len = tl.len(); s = tl.start_rank(); chunk = tl.chunk();
-        gcol = grad_cols + size_t(t) * size_t(K);
-        p = param_ptrs[t] + e0;
-        s1 = s1_ptrs[t] + e0;
-        s2 = ADAM ? s2_ptrs[t] + e0 : nullptr;
-        m = USE_MEAN_TENSOR ? mean_ptrs[t] + e0 : nullptr;
+        gcol = grad_cols + size_t(tl.tensor()) * size_t(K);
+        p = tl.p();
+        s1 = tl.s1();
+        s2 = ADAM ? tl.s2() : nullptr;
+        m = USE_MEAN_TENSOR ? tl.m() : nullptr;
         head = tl.head(head_index<SRC, MEAN, OPT>());
         if (head < 0 || head > len) head = len;
         nvec = (len - head) / VEC;
@@ -203,14 +211,12 @@ struct TileView {
 // U = gradient vectors requested back to back before the first one is consumed.
 template <int DT, int U, int SRC, int MEAN, int OPT>
 __global__ __launch_bounds__(kBlock) void k_step(
-    const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
-    float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
-    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
+    const DeviceTile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
     const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
     using TV = TileView<DT, SRC, MEAN, OPT>;
     constexpr int Q = TV::Q;
     __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
-    const TV tv(load_tile(tiles, blockIdx.x), grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+    const TV tv(load_tile(tiles, blockIdx.x), grad_cols, K);
     for (int vi0 = 0; vi0 < tv.nvec; vi0 += kBlock) {          // same trip count for the whole workgroup
         f32x4 g[Q];
         if constexpr (SRC == SRC_MEAN) tv.averaged_from_mean(g, vi0 + int(threadIdx.x));
@@ -230,9 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_step(
 // 16-byte vector per thread here (tile_elems == kBlock * VEC).
 template <int DT, int U, int MEAN, int OPT>
 __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
-    const cmn_tile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
-    float *const *__restrict__ param_ptrs, float *const *__restrict__ s1_ptrs,
-    float *const *__restrict__ s2_ptrs, float *const *__restrict__ mean_ptrs,
+    const DeviceTile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
     const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int n_tiles) {
     using TV = TileView<DT, SRC_FOLD, MEAN, OPT>;
     constexpr int Q = TV::Q;
@@ -245,7 +249,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
         for (int m = 0; m < M; ++m) {
             const int ti = tile0 + m * W;
             if (ti < n_tiles) {
-                const TV tv(load_tile(tiles, ti), grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                const TV tv(load_tile(tiles, ti), grad_cols, K);
                 tv.template averaged<U>(gbar[m], int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
                 tv.ragged(scale_ptrs, K, inv_k, o);
             }
@@ -254,7 +258,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
         for (int m = 0; m < M; ++m) {
             const int ti = tile0 + m * W;
             if (ti < n_tiles) {
-                const TV tv(load_tile(tiles, ti), grad_cols, param_ptrs, s1_ptrs, s2_ptrs, mean_ptrs, K);
+                const TV tv(load_tile(tiles, ti), grad_cols, K);
                 tv.template apply<false>(gbar[m], 0, K, o, deal_buf);
             }
         }
@@ -265,10 +269,8 @@ template <int DT, int SRC, int MEAN, int OPT>
 inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o, hipStream_t s) {
     constexpr int U = 16;
     hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
-                       ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
-                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<float *const>(p, p->ws.param_ptrs),
-                       ws_ptr<float *const>(p, p->ws.vel_ptrs), ws_ptr<float *const>(p, p->ws.state2_ptrs),
-                       ws_ptr<float *const>(p, p->ws.mean_ptrs), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
+                       ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
+                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
                        p->K, 1.0f / float(p->K), o);
 }
 
@@ -279,10 +281,8 @@ inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t ti
     const int64_t resident = two_phase_grid(p);
     const unsigned grid = unsigned(tile_count < resident ? tile_count : resident);
     hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
-                       ws_ptr<const cmn_tile>(p, p->ws.tiles) + tile_begin,
-                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<float *const>(p, p->ws.param_ptrs),
-                       ws_ptr<float *const>(p, p->ws.vel_ptrs), ws_ptr<float *const>(p, p->ws.state2_ptrs),
-                       ws_ptr<float *const>(p, p->ws.mean_ptrs), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
+                       ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
+                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
                        p->K, 1.0f / float(p->K), o, int(tile_count));
 }
 
