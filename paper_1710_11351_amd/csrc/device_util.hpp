@@ -95,6 +95,13 @@ template <> struct GradT<CMN_I8S> {
     static __device__ __forceinline__ raw encode_vec(const float (&)[16]) { return raw{}; }
 };
 
+// Read of a value that no kernel of this library writes and that is the same for the whole
+// wavefront (an int8 scale): through the constant address space, so that it becomes a scalar
+// load instead of a vector memory instruction with 64 equal addresses.
+__device__ __forceinline__ float load_uniform(const float *p) {
+    return *(const __attribute__((address_space(4))) float *)(p);
+}
+
 template <typename V>
 __device__ __forceinline__ V load_vec(const void *p) {
     return *reinterpret_cast<const V *>(p);

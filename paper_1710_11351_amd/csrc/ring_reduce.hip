@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const void *__restrict__
     if (e < in_chunk)
         fold_all<DT, U>(
             acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
-            [&](int j) { return scale_ptrs[ring_rank(s, j, K)][c]; });
+            [&](int j) { return load_uniform(scale_ptrs[ring_rank(s, j, K)] + c); });
     f32x4 o[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) o[q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
                 if (e < in_chunk)
                     fold_all<DT, U>(
                         acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
-                        [&](int j) { return scale_ptrs[ring_rank(s, j, K)][c]; });
+                        [&](int j) { return load_uniform(scale_ptrs[ring_rank(s, j, K)] + c); });
 #pragma unroll
                 for (int q = 0; q < Q; ++q) stash[m][q] = f32x4{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
                 wave_deal<Q>(stash[m], deal_buf);

@@ -98,7 +98,7 @@ struct TileView {
             for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
             fold_all<DT, U>(
                 gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + e0 + e; },
-                [&](int j) { return scale_ptrs[ring_rank(s, j, K)][chunk]; });
+                [&](int j) { return load_uniform(scale_ptrs[ring_rank(s, j, K)] + chunk); });
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = gb[i] * inv_k;
         }
@@ -189,7 +189,7 @@ struct TileView {
                 for (int j = 0; j < K; ++j) {
                     const int r = ring_rank(s, j, K);
                     acc = acc + G::decode(static_cast<const elem *>(gcol[r])[e0 + e],
-                                          DT == CMN_I8S ? scale_ptrs[r][chunk] : 1.0f);
+                                          DT == CMN_I8S ? load_uniform(scale_ptrs[r] + chunk) : 1.0f);
                 }
                 gb = acc * inv_k;
             }
