@@ -45,7 +45,10 @@ def to_numpy(t):
 
 
 class DeviceCase:
-    """Device tensors of one workload, each tensor its own allocation."""
+    """Device tensors of one workload, each tensor its own allocation.  misalign: every tensor starts
+    that many elements past its allocation; a tuple (even replicas, odd replicas, parameters and
+    optimizer state, mean gradient) gives each group its own offset, so that the streams of a tile
+    share no 16-byte alignment and the kernels fall back to their element-by-element path."""
 
     def __init__(self, c: wl.Config, ring_rotate=1, misalign=0, with_mean=True, adam=False):
         import torch
@@ -53,16 +56,18 @@ class DeviceCase:
         tg = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i8s": torch.int8}[c.grad_dtype]
         self.plan = B.Plan(c.numel, c.K, c.n_chunks, c.align_bytes, c.grad_dtype, ring_rotate)
 
-        def alloc(dtype):
+        mis = misalign if isinstance(misalign, tuple) else (misalign,) * 4
+
+        def alloc(dtype, off):
             out = []
             for n in c.numel:
-                buf = torch.zeros(n + misalign, dtype=dtype, device="cuda")
-                out.append(buf[misalign:])
+                buf = torch.zeros(n + off, dtype=dtype, device="cuda")
+                out.append(buf[off:])
             return out
 
-        self.grads = [alloc(tg) for _ in range(c.K)]
-        self.p, self.v = alloc(torch.float32), alloc(torch.float32)
-        self.m = alloc(torch.float32) if with_mean else None
+        self.grads = [alloc(tg, mis[k % 2]) for k in range(c.K)]
+        self.p, self.v = alloc(torch.float32, mis[2]), alloc(torch.float32, mis[2])
+        self.m = alloc(torch.float32, mis[3]) if with_mean else None
         self.plan.bind(self.grads, self.p, self.v, self.m)
         self.scales = None
         if c.grad_dtype == "i8s":
@@ -70,7 +75,7 @@ class DeviceCase:
             self.plan.bind_scales(self.scales)
         self.s = None
         if adam:
-            self.s = alloc(torch.float32)
+            self.s = alloc(torch.float32, mis[2])
             self.plan.bind_adam(self.s)
 
     def set_state(self, p_host, v_host):

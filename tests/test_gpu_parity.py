@@ -62,6 +62,18 @@ def test_two_phase_rounds_at_small_size(monkeypatch, dtype, opt):
     run_parity(c, steps=1, misalign=1, opt=opt, staged=False)
 
 
+@pytest.mark.parametrize("K", [3, 9])                 # one-pass / two-phase kernel
+@pytest.mark.parametrize("dtype,opt", [("f32", "sgd"), ("f16", "sgd"), ("bf16", "adam"), ("f32", "adam")])
+@pytest.mark.parametrize("mis", [(1, 1, 2, 2), (0, 1, 0, 0), (0, 0, 0, 1), (2, 2, 1, 3)])
+def test_streams_without_a_common_alignment(K, dtype, opt, mis):
+    """Gradients, parameters/state and mean gradient start at different offsets from a 16-byte
+    boundary (or the replicas disagree among themselves): some or all kernel variants find no
+    common alignment and must process whole tiles element by element, with the same bits."""
+    numel = [5, 3000, 0, 1025, 64, 4099]
+    c = wl.custom_config(numel, K=K, n_chunks=4, grad_dtype=dtype, cfg=74, wd=1e-3)
+    run_parity(c, steps=2, misalign=mis, opt=opt)
+
+
 def test_single_replica_is_the_plain_optimizer():
     c = wl.custom_config([3000, 100], K=1, n_chunks=1, cfg=93)
     run_parity(c, steps=2)
