@@ -146,6 +146,7 @@ __device__ __forceinline__ void store_vec(__amdgpu_buffer_rsrc_t r, unsigned byt
 //    with all replicas overwritten; K = 4: 228 -> 174 us).
 constexpr int kStoreStateOnePass = ST_THROUGH;
 constexpr int kStoreStatePhase2 = ST_BACK;
+constexpr int kStoreStateStream = ST_STREAM_THROUGH;   // optimizer-only kernels on models larger than the cache
 constexpr int kStoreAverage = ST_STREAM_THROUGH;
 constexpr int kStoreReducedOnePass = ST_THROUGH;   // ring reduce, one-pass
 constexpr int kStoreReducedPhase2 = ST_BACK;       // ring reduce, two-phase (scale+unpack reads it next; nt: no gain)

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kBlock) void k_pack(const long long *__restrict__ o
     }
 }
 
-template <bool LDS>
+template <bool LDS, bool STREAM>
 __global__ __launch_bounds__(kBlock) void k_scale_unpack(const long long *__restrict__ off_g,
                                                          float *const *__restrict__ mean_g,
                                                          const float *__restrict__ reduced, int T, long long N,
@@ -106,7 +106,9 @@ __global__ __launch_bounds__(kBlock) void k_scale_unpack(const long long *__rest
         if (t < 0 || i >= off(t + 1)) t = find_tensor(off, T, i);
         float *d = ptr(t) + (i - off(t));
         if (i + 4 <= off(t + 1) && (reinterpret_cast<uintptr_t>(d) & 15) == 0) {
-            *reinterpret_cast<f32x4 *>(d) = g;   // plain: the optimizer reads it next, out of the memory-side cache
+            // plain: the optimizer reads it next, out of the memory-side cache (unless the model outgrows it)
+            if (STREAM) __builtin_nontemporal_store(g, reinterpret_cast<f32x4 *>(d));
+            else *reinterpret_cast<f32x4 *>(d) = g;
         } else {
             int tt = t;
 #pragma unroll
@@ -169,11 +171,12 @@ extern "C" int cmn_scale_unpack(const cmn_plan *plan, const float *reduced, void
     const long long *off = ws_ptr<const long long>(plan, plan->ws.off_table);
     float *const *mean = ws_ptr<float *const>(plan, plan->ws.mean_ptrs);
     const float inv_k = 1.0f / float(plan->K);
-    if (lds)
-        hipLaunchKernelGGL((k_scale_unpack<true>), dim3(unsigned(nx)), dim3(kBlock), shm, s, off, mean, reduced, T,
-                           (long long)plan->N, inv_k);
-    else
-        hipLaunchKernelGGL((k_scale_unpack<false>), dim3(unsigned(nx)), dim3(kBlock), shm, s, off, mean, reduced, T,
-                           (long long)plan->N, inv_k);
+    const bool big = beyond_cache(4.0 * double(plan->N));
+#define CMN_LAUNCH_UNPACK(LDS, STREAM)                                                                       \
+    hipLaunchKernelGGL((k_scale_unpack<LDS, STREAM>), dim3(unsigned(nx)), dim3(kBlock), shm, s, off, mean, reduced, T, \
+                       (long long)plan->N, inv_k)
+    if (lds) { if (big) CMN_LAUNCH_UNPACK(true, true); else CMN_LAUNCH_UNPACK(true, false); }
+    else { if (big) CMN_LAUNCH_UNPACK(false, true); else CMN_LAUNCH_UNPACK(false, false); }
+#undef CMN_LAUNCH_UNPACK
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }

@@ -34,6 +34,11 @@ struct DeviceTile {
 };
 static_assert(sizeof(DeviceTile) == 64, "one scalar cache line");
 
+// Whether a working set that one kernel writes and the next one reads is too large for the 256 MB
+// memory-side cache to carry it over (measured boundary: 306 MB still profits from the cache,
+// 1.7 GB profits from streaming loads and stores instead).
+inline bool beyond_cache(double bytes) { return bytes > 2.0 * 256.0 * 1024.0 * 1024.0; }
+
 inline int elem_bytes(int dtype) { return dtype == CMN_F32 ? 4 : dtype == CMN_I8S ? 1 : 2; }
 inline int vec_elems(int dtype) { return 16 / elem_bytes(dtype); }
 

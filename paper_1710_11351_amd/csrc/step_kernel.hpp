@@ -108,22 +108,26 @@ struct TileView {
     }
 
     // The same from the bound mean-gradient tensor (optimizer-only kernels, Q = 1).
+    template <bool STREAM>
     __device__ __forceinline__ void averaged_from_mean(f32x4 (&out)[Q], int vi) const {
         static_assert(SRC != SRC_MEAN || Q == 1, "the mean gradient is fp32");
-        out[0] = vi < nvec ? load_vec<f32x4>(m + head + vi * 4) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        out[0] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (vi < nvec) out[0] = STREAM ? load_stream<f32x4>(m + head + vi * 4) : load_vec<f32x4>(m + head + vi * 4);
     }
 
     // Optimizer on the thread's Q float4s in dealt order (g from averaged() of the same round,
     // vi0 = number of the round's first vector): parameter and state fetched here; results, and
     // the averaged gradient where asked for, stored with the policy of the calling kernel's kind.
-    template <bool ONE_PASS = true>
+    // STREAM: parameters and state are too large to stay in the memory-side cache until the next
+    // step, so they are read and written as streaming data.
+    template <bool ONE_PASS = true, bool STREAM = false>
     __device__ __forceinline__ void apply(const f32x4 (&g)[Q], int vi0, int K, const OptArgs &o, f32x4 *deal_buf) const {
         const unsigned bytes = unsigned(len) * 4u;
         const __amdgpu_buffer_rsrc_t p_out = make_rsrc(p, bytes);
         const __amdgpu_buffer_rsrc_t s1_out = make_rsrc(s1, bytes);
         const __amdgpu_buffer_rsrc_t s2_out = make_rsrc(s2, ADAM ? bytes : 0u);
         const __amdgpu_buffer_rsrc_t m_out = make_rsrc(m, MEAN == CMN_MEAN_TO_MEAN_GRADS ? bytes : 0u);
-        constexpr int ST = ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2;
+        constexpr int ST = STREAM ? kStoreStateStream : ONE_PASS ? kStoreStateOnePass : kStoreStatePhase2;
         const unsigned end = unsigned(nvec) * VEC;             // floats of the tile covered by whole vectors
         unsigned x[Q];
         f32x4 pv[Q], s1v[Q], s2v[Q];
@@ -131,9 +135,9 @@ struct TileView {
         for (int q = 0; q < Q; ++q) {
             x[q] = unsigned(vi0) * VEC + dealt_offset<Q>(q);   // multiple of 4, like end
             if (x[q] < end) {
-                pv[q] = load_vec<f32x4>(p + head + x[q]);
-                s1v[q] = load_vec<f32x4>(s1 + head + x[q]);
-                if (ADAM) s2v[q] = load_vec<f32x4>(s2 + head + x[q]);
+                pv[q] = STREAM ? load_stream<f32x4>(p + head + x[q]) : load_vec<f32x4>(p + head + x[q]);
+                s1v[q] = STREAM ? load_stream<f32x4>(s1 + head + x[q]) : load_vec<f32x4>(s1 + head + x[q]);
+                if (ADAM) s2v[q] = STREAM ? load_stream<f32x4>(s2 + head + x[q]) : load_vec<f32x4>(s2 + head + x[q]);
             }
         }
 #pragma unroll
@@ -209,7 +213,7 @@ struct TileView {
 
 // Streaming kernel: one workgroup per tile, everything in one go.
 // U = gradient vectors requested back to back before the first one is consumed.
-template <int DT, int U, int SRC, int MEAN, int OPT>
+template <int DT, int U, int SRC, int MEAN, int OPT, bool STREAM = false>
 __global__ __launch_bounds__(kBlock) void k_step(
     const DeviceTile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
     const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
@@ -219,9 +223,9 @@ __global__ __launch_bounds__(kBlock) void k_step(
     const TV tv(load_tile(tiles, blockIdx.x), grad_cols, K);
     for (int vi0 = 0; vi0 < tv.nvec; vi0 += kBlock) {          // same trip count for the whole workgroup
         f32x4 g[Q];
-        if constexpr (SRC == SRC_MEAN) tv.averaged_from_mean(g, vi0 + int(threadIdx.x));
+        if constexpr (SRC == SRC_MEAN) tv.template averaged_from_mean<STREAM>(g, vi0 + int(threadIdx.x));
         else tv.template averaged<U>(g, vi0 + int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
-        tv.apply(g, vi0, K, o, deal_buf);
+        tv.template apply<true, STREAM>(g, vi0, K, o, deal_buf);
     }
     tv.ragged(scale_ptrs, K, inv_k, o);
 }
@@ -265,10 +269,10 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     }
 }
 
-template <int DT, int SRC, int MEAN, int OPT>
+template <int DT, int SRC, int MEAN, int OPT, bool STREAM = false>
 inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o, hipStream_t s) {
     constexpr int U = 16;
-    hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT, STREAM>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
                        ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
                        ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
                        p->K, 1.0f / float(p->K), o);
@@ -339,7 +343,12 @@ inline int launch_optimizer(const cmn_plan *plan, const OptArgs &o, void *stream
     if (!plan->have_opt || !plan->have_mean) return CMN_EUNBOUND;
     if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
     if (plan->n_tiles == 0) return CMN_OK;
-    launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
+    // mean gradient, parameters and state of a large model (VGG-16: 1.7 GB) cannot stay in the 256 MB
+    // memory-side cache from one kernel to the next: stream them (VGG-16 525 -> 480 us); a small
+    // model's do stay, and streaming them would cost it 8 % (ResNet-50 77 -> 83 us)
+    const bool big = beyond_cache(double(plan->N) * (OPT == OPT_ADAM ? 16.0 : 12.0));
+    if (big) launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT, true>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
+    else launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT, false>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }
 

@@ -276,6 +276,11 @@ def test_config5_vgg16_k16_weight_decay_full_size():
     run_parity(wl.config(5), steps=2)
 
 
+def test_config5_vgg16_k16_adam_staged_full_size():
+    """The optimizer-only kernels on a model larger than the memory-side cache (streaming loads and stores)."""
+    run_parity(wl.config(5), steps=1, opt="adam", fused=False)
+
+
 def test_f16_storage_within_2e3_of_unquantised_fp32():
     """Config 4's value distribution (1 % of elements at 100x) on a smaller list: the mean gradient
     from fp16-stored gradients stays within 2e-3 of the float64 mean b of the un-quantised fp32
