@@ -241,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void k_step(
 template <int DT, int U, int MEAN, int OPT>
 __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     const DeviceTile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
-    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int n_tiles) {
+    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int n_tiles, int stream_state) {
     using TV = TileView<DT, SRC_FOLD, MEAN, OPT>;
     constexpr int Q = TV::Q;
     constexpr int M = kStashFloats / TV::VEC;
@@ -263,7 +263,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
             const int ti = tile0 + m * W;
             if (ti < n_tiles) {
                 const TV tv(load_tile(tiles, ti), grad_cols, K);
-                tv.template apply<false>(gbar[m], 0, K, o, deal_buf);
+                if (stream_state) tv.template apply<false, true>(gbar[m], 0, K, o, deal_buf);
+                else tv.template apply<false, false>(gbar[m], 0, K, o, deal_buf);
             }
         }
     }
@@ -287,7 +288,9 @@ inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t ti
     hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
                        ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
                        ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
-                       p->K, 1.0f / float(p->K), o, int(tile_count));
+                       p->K, 1.0f / float(p->K), o, int(tile_count),
+                       // parameters and state too large for the memory-side cache: stream them (VGG-16 1785 -> 1733 us)
+                       int(beyond_cache(double(p->N) * (OPT == OPT_ADAM ? 12.0 : 8.0))));
 }
 
 // Fused step (SRC_FOLD) over tensors [t0, t1): validation shared by the SGD and Adam entry points.
@@ -316,9 +319,14 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     const int64_t n_launch = (n + slots - 1) / slots, per_launch = (n + n_launch - 1) / n_launch;
 #define CMN_STEP_CASE(DT, MEAN)                                                                          \
     do {                                                                                                 \
-        if (!two_phase) launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s);                        \
-        else for (int64_t b0 = 0; b0 < n; b0 += per_launch)                                              \
-            launch_k_two_phase<DT, MEAN, OPT>(plan, b + b0, n - b0 < per_launch ? n - b0 : per_launch, o, s); \
+        if constexpr (DT != CMN_I8S) {      /* int8 storage never takes the two-phase kernel */          \
+            if (two_phase) {                                                                             \
+                for (int64_t b0 = 0; b0 < n; b0 += per_launch)                                           \
+                    launch_k_two_phase<DT, MEAN, OPT>(plan, b + b0, n - b0 < per_launch ? n - b0 : per_launch, o, s); \
+                break;                                                                                   \
+            }                                                                                            \
+        }                                                                                                \
+        launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s);                                        \
     } while (0)
 #define CMN_STEP_DTYPE(DT)                                                                  \
     do {                                                                                    \
