@@ -213,19 +213,24 @@ struct TileView {
 
 // Streaming kernel: one workgroup per tile, everything in one go.
 // U = gradient vectors requested back to back before the first one is consumed.
-template <int DT, int U, int SRC, int MEAN, int OPT, bool STREAM = false>
+template <int DT, int U, int SRC, int MEAN, int OPT>
 __global__ __launch_bounds__(kBlock) void k_step(
     const DeviceTile *__restrict__ tiles, const void *const *__restrict__ grad_cols,
-    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o) {
+    const float *const *__restrict__ scale_ptrs, int K, float inv_k, OptArgs o, int stream_state) {
     using TV = TileView<DT, SRC, MEAN, OPT>;
     constexpr int Q = TV::Q;
     __shared__ f32x4 deal_buf[deal_buffer_vectors<Q>()];
     const TV tv(load_tile(tiles, blockIdx.x), grad_cols, K);
     for (int vi0 = 0; vi0 < tv.nvec; vi0 += kBlock) {          // same trip count for the whole workgroup
         f32x4 g[Q];
-        if constexpr (SRC == SRC_MEAN) tv.template averaged_from_mean<STREAM>(g, vi0 + int(threadIdx.x));
-        else tv.template averaged<U>(g, vi0 + int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
-        tv.template apply<true, STREAM>(g, vi0, K, o, deal_buf);
+        if constexpr (SRC == SRC_MEAN) {
+            if (stream_state) tv.template averaged_from_mean<true>(g, vi0 + int(threadIdx.x));
+            else tv.template averaged_from_mean<false>(g, vi0 + int(threadIdx.x));
+        } else {
+            tv.template averaged<U>(g, vi0 + int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
+        }
+        if (stream_state) tv.template apply<true, true>(g, vi0, K, o, deal_buf);
+        else tv.template apply<true, false>(g, vi0, K, o, deal_buf);
     }
     tv.ragged(scale_ptrs, K, inv_k, o);
 }
@@ -270,13 +275,22 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     }
 }
 
-template <int DT, int SRC, int MEAN, int OPT, bool STREAM = false>
+// Parameters and optimizer state (and, for the optimizer-only kernels, the mean gradient) of a
+// large model cannot stay in the memory-side cache from one kernel to the next: then they are
+// streamed (VGG-16, 1.1-1.7 GB: cmn_momentum_sgd 525 -> 480 us, fused step 1785 -> 1730 us).  A small
+// model's do stay, and streaming them would cost it 8 % (ResNet-50, 306 MB: 77 -> 83 us).
+template <int SRC, int OPT>
+inline int stream_state(const cmn_plan *p) {
+    return int(beyond_cache(double(p->N) * ((OPT == OPT_ADAM ? 12.0 : 8.0) + (SRC == SRC_MEAN ? 4.0 : 0.0))));
+}
+
+template <int DT, int SRC, int MEAN, int OPT>
 inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o, hipStream_t s) {
     constexpr int U = 16;
-    hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT, STREAM>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
                        ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
                        ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
-                       p->K, 1.0f / float(p->K), o);
+                       p->K, 1.0f / float(p->K), o, stream_state<SRC, OPT>(p));
 }
 
 template <int DT, int MEAN, int OPT>
@@ -288,9 +302,7 @@ inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t ti
     hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
                        ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
                        ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
-                       p->K, 1.0f / float(p->K), o, int(tile_count),
-                       // parameters and state too large for the memory-side cache: stream them (VGG-16 1785 -> 1733 us)
-                       int(beyond_cache(double(p->N) * (OPT == OPT_ADAM ? 12.0 : 8.0))));
+                       p->K, 1.0f / float(p->K), o, int(tile_count), stream_state<SRC_FOLD, OPT>(p));
 }
 
 // Fused step (SRC_FOLD) over tensors [t0, t1): validation shared by the SGD and Adam entry points.
@@ -351,12 +363,7 @@ inline int launch_optimizer(const cmn_plan *plan, const OptArgs &o, void *stream
     if (!plan->have_opt || !plan->have_mean) return CMN_EUNBOUND;
     if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
     if (plan->n_tiles == 0) return CMN_OK;
-    // mean gradient, parameters and state of a large model (VGG-16: 1.7 GB) cannot stay in the 256 MB
-    // memory-side cache from one kernel to the next: stream them (VGG-16 525 -> 480 us); a small
-    // model's do stay, and streaming them would cost it 8 % (ResNet-50 77 -> 83 us)
-    const bool big = beyond_cache(double(plan->N) * (OPT == OPT_ADAM ? 16.0 : 12.0));
-    if (big) launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT, true>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
-    else launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT, false>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
+    launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }
 
