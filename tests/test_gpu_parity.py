@@ -263,6 +263,36 @@ def test_average_is_handed_back_to_every_replica(dtype, misalign, K):
             assert_bit_equal(a, b, f"step {step} state {t}")
 
 
+@pytest.mark.parametrize("K", [3, 9])             # one-pass kernel / two-phase persistent kernel
+@pytest.mark.parametrize("staged", [False, True])
+def test_mean_gradient_may_overwrite_replica_0(K, staged):
+    """The mean-gradient tensors may be replica 0's own float32 gradient tensors: every kernel
+    has read an element's K gradients before it writes the element's average."""
+    import oracle
+    import torch
+    from parity_util import DeviceCase, assert_bit_equal, gen_all_grads
+    numel = [3000, 0, 77, 4096, 1, 2050]
+    c = wl.custom_config(numel, K=K, n_chunks=4, cfg=73, wd=1e-3)
+    dc = DeviceCase(c, misalign=1)
+    dc.plan.bind(dc.grads, dc.p, dc.v, dc.grads[0])
+    p_o, v_o = [x.copy() for x in wl.gen_params(c)], wl.gen_velocity(c)
+    dc.set_state(p_o, v_o)
+    for step in range(2):
+        grads = gen_all_grads(c, step)
+        for k in range(c.K):
+            dc.set_grads(k, grads[k])
+        mean_o = oracle.allreduce_step(grads, p_o, v_o, c.n_chunks, c.lr, c.mu, c.wd)
+        if staged:
+            packed = torch.empty(c.K * dc.plan.L, dtype=torch.float32, device="cuda")
+            reduced = torch.empty(dc.plan.L, dtype=torch.float32, device="cuda")
+            dc.plan.pack(packed); dc.plan.ring_reduce(packed, reduced); dc.plan.scale_unpack(reduced)
+            dc.plan.momentum_sgd(c.lr, c.mu, c.wd)
+        else:
+            dc.plan.allreduce_step(c.lr, c.mu, c.wd, write_mean_grad=True)
+        for t, (a, b) in enumerate(zip(dc.get(dc.grads[0]) + dc.get(dc.p) + dc.get(dc.v), mean_o + p_o + v_o)):
+            assert_bit_equal(a, b, f"step {step} tensor {t}")
+
+
 # ---- the benchmark workloads at full size, in the launch configuration bench.py times ----
 def test_config3_resnet50_k32_full_size():
     run_parity(wl.config(3), steps=3)
