@@ -182,14 +182,14 @@ def main():
     if not args.no_cpu and (args.opt, args.mean_dest) == ("sgd", 0):
         import oracle                                # CPU baseline leg only
         threads = oracle.max_threads()
-        reps, times = 5, []
-        for _ in range(reps):                        # the whole workload, not a sample: it takes well under a second
+        times = []
+        while len(times) < 3 or (sum(times) < 10.0 and len(times) < 40):   # whole steps, about 10 s of them
             p_o, v_o = [x.copy() for x in p_h], [x.copy() for x in v_h]
             t1 = time.perf_counter()
             oracle.allreduce_step(host_grads, p_o, v_o, c.n_chunks, c.lr, c.mu, c.wd, dtype=c.grad_dtype,
                                   align_bytes=c.align_bytes)
             times.append(time.perf_counter() - t1)
-        dt = float(np.mean(times))
+        dt, reps = float(np.mean(times)), len(times)
         cpu = {"value": round(abytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
                "sample": f"{reps} full steps of {c.name} (all {c.N} elements, K={c.K}), mean {dt:.2f} s each; "
                          f"OpenMP over ring chunks in the fold, the other steps single-threaded",
