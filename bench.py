@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per launch of the fused kernel at config 3 read by rocprofv3 --pmc
 # (FETCH_SIZE, WRITE_SIZE), scaled by the same counters' reading of a plain copy of
 # known size (scale 2.0 for FETCH_SIZE, 1.0 for WRITE_SIZE).  Source: profiles/allreduce_step_resnet50_k32_pmc.txt
-MEASURED_TRAFFIC_BYTES = {3: 3_691_400_000}
+MEASURED_TRAFFIC_BYTES = {3: 3_691_800_000}
 
 
 def log(*a):
