@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
     for name in ("cmn_plan_total_elems", "cmn_plan_padded_elems", "cmn_plan_chunk_elems", "cmn_plan_tile_count"):
         getattr(L, name).restype = ctypes.c_int64
         getattr(L, name).argtypes = [vp]
+    L.cmn_plan_step_kernel_kind.restype = ctypes.c_int
+    L.cmn_plan_step_kernel_kind.argtypes = [vp]
     L.cmn_plan_workspace_bytes.restype = ctypes.c_size_t
     L.cmn_plan_workspace_bytes.argtypes = [vp]
     L.cmn_plan_describe_tiles.restype = ctypes.c_int
@@ -164,6 +166,10 @@ def cmn_plan_tile_count(h) -> int:
     return lib().cmn_plan_tile_count(h)
 
 
+def cmn_plan_step_kernel_kind(h) -> int:
+    return lib().cmn_plan_step_kernel_kind(h)
+
+
 def cmn_plan_workspace_bytes(h) -> int:
     return lib().cmn_plan_workspace_bytes(h)
 
@@ -253,6 +259,7 @@ class Plan:
         self.chunk_elems = cmn_plan_chunk_elems(self.h)
         self.tile_count = cmn_plan_tile_count(self.h)
         self.workspace_bytes = cmn_plan_workspace_bytes(self.h)
+        self.step_kernel_kind = cmn_plan_step_kernel_kind(self.h)
         self._keep = None
 
     def close(self) -> None:

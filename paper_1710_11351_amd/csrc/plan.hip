@@ -137,8 +137,24 @@ int64_t two_phase_grid(const cmn_plan *p) {
     return p->grid_limit > 0 && p->grid_limit < resident ? p->grid_limit : resident;
 }
 
-bool prefer_two_phase(const cmn_plan *p) {
-    return !p->one_pass_only && p->K >= 8 && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
+// Which kernel serves a plan.  The two-phase kernels need one vector per thread and tile and
+// are not built for int8 storage (its decode arithmetic wants the one-pass kernel's occupancy).
+// Where both kinds apply the choice follows measurements on MI355X:
+//  - ring reduce: two-phase from 8 replicas on;
+//  - fused step, parameters and state beyond the memory-side cache (VGG-16): the same;
+//  - fused step, parameters and state cache-resident (ResNet-50): their stores disturb the
+//    gradient reads less, and the one-pass kernel stays ahead until the replicas deliver about
+//    56 bytes per element (fp32: 14 replicas, 16-bit: 28).
+static bool two_phase_possible(const cmn_plan *p) {
+    return p->step_mode != STEP_ONE_PASS && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
+}
+bool prefer_two_phase_reduce(const cmn_plan *p) {
+    return two_phase_possible(p) && (p->step_mode == STEP_TWO_PHASE || p->K >= 8);
+}
+bool prefer_two_phase_step(const cmn_plan *p) {
+    if (!two_phase_possible(p)) return false;
+    if (p->step_mode == STEP_TWO_PHASE) return true;
+    return beyond_cache(8.0 * double(p->N)) ? p->K >= 8 : p->K * elem_bytes(p->dtype) >= 56;
 }
 
 int check_launch(const cmn_plan *p) {
@@ -192,7 +208,8 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
         if (v >= 1 && v <= 64) iters = v;
     }
     p->tile_elems = kBlock * vec_elems(grad_dtype) * iters;
-    if (const char *k = std::getenv("CMN_STEP_KERNEL")) p->one_pass_only = std::strcmp(k, "stream") == 0;
+    if (const char *k = std::getenv("CMN_STEP_KERNEL"))
+        p->step_mode = std::strcmp(k, "stream") == 0 ? STEP_ONE_PASS : std::strcmp(k, "two_phase") == 0 ? STEP_TWO_PHASE : STEP_AUTO;
     if (const char *k = std::getenv("CMN_TWO_PHASE_GRID")) p->grid_limit = std::atoi(k) > 0 ? std::atoi(k) : 0;
     try {
         p->first_tile.assign(size_t(n_tensors) + 1, 0);
@@ -217,6 +234,7 @@ int64_t cmn_plan_total_elems(const cmn_plan *p) { return p ? p->N : -1; }
 int64_t cmn_plan_padded_elems(const cmn_plan *p) { return p ? p->L : -1; }
 int64_t cmn_plan_chunk_elems(const cmn_plan *p) { return p ? p->chunk_elems : -1; }
 int64_t cmn_plan_tile_count(const cmn_plan *p) { return p ? p->n_tiles : -1; }
+int cmn_plan_step_kernel_kind(const cmn_plan *p) { return p ? (prefer_two_phase_step(p) ? 2 : 1) : -1; }
 size_t cmn_plan_workspace_bytes(const cmn_plan *p) { return p ? p->ws.total : 0; }
 
 static int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows, unsigned elem_bytes) {

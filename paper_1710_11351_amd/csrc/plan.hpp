@@ -21,6 +21,8 @@ constexpr int kTileIters = 1;
 // write phase (leaves ~50 of the 256 registers available at two waves per SIMD for the fold).
 constexpr int kStashFloats = 200;
 
+enum { STEP_AUTO = 0, STEP_ONE_PASS = 1, STEP_TWO_PHASE = 2 };
+
 // What the tensor-space kernels read per tile: the fields of the public cmn_tile plus the tile's
 // own addresses, so that one 64-byte scalar load yields everything but the gradient pointers
 // (looking p, state and mean gradient up by tensor index would put three more dependent scalar
@@ -62,7 +64,7 @@ struct cmn_plan {
     int T = 0, K = 1, C = 1, align_bytes = 256, dtype = CMN_F32, ring_rotate = 1;
     int tile_elems = 0;
     // launch-shape knobs, fixed at creation from the environment (results never depend on them)
-    bool one_pass_only = false;          // CMN_STEP_KERNEL=stream: never pick the two-phase kernels
+    int step_mode = cmn::STEP_AUTO;      // CMN_STEP_KERNEL=stream | two_phase: force one kind of kernel where it applies
     int grid_limit = 0;                  // CMN_TWO_PHASE_GRID: at most this many persistent workgroups (0: 2 per CU)
     std::vector<int64_t> numel;  // [T]
     std::vector<int64_t> off;    // [T+1]
@@ -89,7 +91,8 @@ int check_launch(const cmn_plan *p);
 // the two-phase kernels win from K = 8 replicas on and lose for int8 storage.
 // CMN_STEP_KERNEL=stream in the environment forces the one-pass kernels (A/B runs, tests).
 int device_compute_units();
-bool prefer_two_phase(const cmn_plan *p);
+bool prefer_two_phase_reduce(const cmn_plan *p);
+bool prefer_two_phase_step(const cmn_plan *p);
 int64_t two_phase_grid(const cmn_plan *p);
 
 template <typename T>

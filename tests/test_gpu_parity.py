@@ -31,7 +31,7 @@ def test_unaligned_base_pointers(dtype, misalign):
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("misalign", [0, 1, 3])
-def test_ragged_unaligned_lists_through_the_two_phase_kernel(dtype, misalign):
+def test_ragged_unaligned_lists_with_ten_replicas(dtype, misalign):
     numel = [5, 0, 5000, 1, 64, 12345, 7, 0, 2049, 3, 70000]
     c = wl.custom_config(numel, K=10, n_chunks=7, grad_dtype=dtype, cfg=77, wd=1e-3)
     run_parity(c, steps=2, misalign=misalign)
@@ -41,7 +41,7 @@ def test_ragged_unaligned_lists_through_the_two_phase_kernel(dtype, misalign):
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 def test_launch_shape_knobs_do_not_change_results(monkeypatch, env, dtype):
     """The two environment knobs read at plan creation pick another kernel or tile size; the result
-    stays the oracle's, bit for bit (K = 12 would otherwise take the two-phase kernels)."""
+    stays the oracle's, bit for bit (also under a forced kernel kind)."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     numel = [5, 0, 5000, 1, 64, 12345, 7, 2049, 3, 30000]
@@ -62,7 +62,7 @@ def test_two_phase_rounds_at_small_size(monkeypatch, dtype, opt):
     run_parity(c, steps=1, misalign=1, opt=opt, staged=False)
 
 
-@pytest.mark.parametrize("K", [3, 9])                 # one-pass / two-phase kernel
+@pytest.mark.parametrize("K", [3, 9])                 # a few and several replicas (either kernel kind is also forced, see conftest.py)
 @pytest.mark.parametrize("dtype,opt", [("f32", "sgd"), ("f16", "sgd"), ("bf16", "adam"), ("f32", "adam")])
 @pytest.mark.parametrize("mis", [(1, 1, 2, 2), (0, 1, 0, 0), (0, 0, 0, 1), (2, 2, 1, 3)])
 def test_streams_without_a_common_alignment(K, dtype, opt, mis):
@@ -162,7 +162,7 @@ def test_bf16_storage_within_8e3_of_unquantised_fp32():
         assert np.max(np.abs(got[t] - want)) > 0
 
 
-@pytest.mark.parametrize("K", [2, 8])             # one-pass kernel / two-phase persistent kernel
+@pytest.mark.parametrize("K", [2, 8])             # a few and several replicas (either kernel kind is also forced, see conftest.py)
 def test_special_values_propagate(K):
     import torch
     from paper_1710_11351_amd import binding as B
@@ -235,7 +235,7 @@ def test_range_arguments_are_validated():
     assert B.cmn_allreduce_step_range(dc.plan.h, 1, 1, .1, .9, 0., 0) == B.CMN_OK      # empty range: no-op
 
 
-@pytest.mark.parametrize("K", [5, 9])             # one-pass kernel / two-phase persistent kernel
+@pytest.mark.parametrize("K", [5, 9])             # a few and several replicas (either kernel kind is also forced, see conftest.py)
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("misalign", [0, 1])
 def test_average_is_handed_back_to_every_replica(dtype, misalign, K):
@@ -263,7 +263,7 @@ def test_average_is_handed_back_to_every_replica(dtype, misalign, K):
             assert_bit_equal(a, b, f"step {step} state {t}")
 
 
-@pytest.mark.parametrize("K", [3, 9])             # one-pass kernel / two-phase persistent kernel
+@pytest.mark.parametrize("K", [3, 9])             # a few and several replicas (either kernel kind is also forced, see conftest.py)
 @pytest.mark.parametrize("staged", [False, True])
 def test_mean_gradient_may_overwrite_replica_0(K, staged):
     """The mean-gradient tensors may be replica 0's own float32 gradient tensors: every kernel
@@ -345,7 +345,7 @@ def test_config3_resnet50_k32_adam_full_size():
     run_parity(wl.config(3), steps=2, opt="adam", staged=False)
 
 
-@pytest.mark.parametrize("K", [4, 8])            # one-pass kernel / two-phase persistent kernel
+@pytest.mark.parametrize("K", [4, 8])            # a few and several replicas (either kernel kind is also forced, see conftest.py)
 def test_range_steps_replayed_from_a_hip_graph_match_eager(K):
     """A launch-bound sequence of small per-layer-group steps captured once into a HIP graph
     and replayed must give the same bits as eager launches, on every replay (the library
