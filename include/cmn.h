@@ -117,10 +117,11 @@ int64_t cmn_plan_padded_elems(const cmn_plan *plan); /* L = n_chunks * chunk_ele
 int64_t cmn_plan_chunk_elems(const cmn_plan *plan);  /* roundup(ceil(N / n_chunks), align_bytes)  */
 int64_t cmn_plan_tile_count(const cmn_plan *plan);   /* number of cmn_tile work units             */
 size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_bind needs (>= 256) */
-/* Which kernel kind the fused steps launch for this plan (a tuning decision that never changes
- * results; for benchmarks and profiles): 1 = one pass, a workgroup per tile; 2 = persistent grid
- * that reads first and writes afterwards; -1 if plan is NULL. */
-int cmn_plan_step_kernel_kind(const cmn_plan *plan);
+/* Which kernel kind the fused step launches for this plan with MomentumSGD (adam == 0) or Adam
+ * (adam != 0): a tuning decision that never changes results; for benchmarks and profiles.
+ * 1 = one pass, a workgroup per tile; 2 = persistent grid that reads first and writes
+ * afterwards; -1 if plan is NULL. */
+int cmn_plan_step_kernel_kind(const cmn_plan *plan, int adam);
 
 /* Pure host: compute the work-unit table that cmn_plan_bind would upload for these
  * pointer arrays (same meaning as in cmn_plan_bind; addresses are only inspected,

@@ -188,7 +188,7 @@ def test_range_and_adam_argument_checks():
 
 def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     """Two-phase fused kernel from about 56 gradient bytes per element while parameters and state
-    fit the memory-side cache, from 8 replicas beyond it, never for int8; the environment can force
+    fit the memory-side cache, from 32 bytes beyond it, never for int8; the environment can force
     either kind where it applies."""
     from paper_1710_11351_amd import workloads as wl
     monkeypatch.delenv("CMN_STEP_KERNEL", raising=False)
@@ -197,6 +197,9 @@ def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     assert [kind(small, K) for K in (4, 8, 13, 14, 32)] == [1, 1, 1, 2, 2]
     assert [kind(small, K, "f16") for K in (16, 27, 28, 128)] == [1, 1, 2, 2]
     assert [kind(big, K) for K in (4, 7, 8, 16)] == [1, 1, 2, 2]
+    assert [kind(big, K, "bf16") for K in (8, 15, 16)] == [1, 1, 2]
+    adam = lambda numel, K, dt="f32": B.Plan(numel, K, K, 256, dt).adam_step_kernel_kind
+    assert [adam(small, K) for K in (4, 7, 8, 32)] == [1, 1, 2, 2]     # both moments: 306 MB, beyond the cache
     assert kind(small, 128, "i8s") == 1
     assert B.cmn_plan_step_kernel_kind(None) == -1
     monkeypatch.setenv("CMN_STEP_KERNEL", "two_phase")
