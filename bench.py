@@ -209,7 +209,7 @@ def main():
                    "entry": "cmn_allreduce_adam_step" if args.opt == "adam" else "cmn_allreduce_step"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "kernel": "k_step_two_phase" if (plan.adam_step_kernel_kind if args.opt == "adam" else plan.step_kernel_kind) == 2
+                     "kernel": "k_step_two_phase" if B.cmn_plan_step_kernel_kind(plan.h, args.opt == "adam", args.mean_dest) == 2
                                else "k_step",
                      "algorithmic_bytes": abytes,
                      "kernel_us": round(kern_ms * 1e3, 2), "device_copy_GBps": round(copy_gbps, 1)},

@@ -65,7 +65,7 @@ def lib() -> ctypes.CDLL:
         getattr(L, name).restype = ctypes.c_int64
         getattr(L, name).argtypes = [vp]
     L.cmn_plan_step_kernel_kind.restype = ctypes.c_int
-    L.cmn_plan_step_kernel_kind.argtypes = [vp, ctypes.c_int]
+    L.cmn_plan_step_kernel_kind.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     L.cmn_plan_workspace_bytes.restype = ctypes.c_size_t
     L.cmn_plan_workspace_bytes.argtypes = [vp]
     L.cmn_plan_describe_tiles.restype = ctypes.c_int
@@ -166,8 +166,8 @@ def cmn_plan_tile_count(h) -> int:
     return lib().cmn_plan_tile_count(h)
 
 
-def cmn_plan_step_kernel_kind(h, adam: int = 0) -> int:
-    return lib().cmn_plan_step_kernel_kind(h, int(adam))
+def cmn_plan_step_kernel_kind(h, adam: int = 0, mean_dest: int = 0) -> int:
+    return lib().cmn_plan_step_kernel_kind(h, int(adam), int(mean_dest))
 
 
 def cmn_plan_workspace_bytes(h) -> int:
@@ -259,8 +259,8 @@ class Plan:
         self.chunk_elems = cmn_plan_chunk_elems(self.h)
         self.tile_count = cmn_plan_tile_count(self.h)
         self.workspace_bytes = cmn_plan_workspace_bytes(self.h)
-        self.step_kernel_kind = cmn_plan_step_kernel_kind(self.h, 0)      # with MomentumSGD
-        self.adam_step_kernel_kind = cmn_plan_step_kernel_kind(self.h, 1)
+        self.step_kernel_kind = cmn_plan_step_kernel_kind(self.h, 0, 0)      # MomentumSGD, average not stored
+        self.adam_step_kernel_kind = cmn_plan_step_kernel_kind(self.h, 1, 0)
         self._keep = None
 
     def close(self) -> None:

@@ -145,18 +145,20 @@ int64_t two_phase_grid(const cmn_plan *p) {
 //    they end in the 256 MB memory-side cache, so with cache-resident state (ResNet-50 with
 //    MomentumSGD, 204 MB) the one-pass kernel stays ahead until the replicas deliver about 56
 //    bytes per element (fp32: 14 replicas, 16-bit: 28); with state beyond the cache (ResNet-50
-//    with Adam, 306 MB; VGG-16) the two-phase kernel wins from about 32 bytes per element.
+//    with Adam, 306 MB; VGG-16) the two-phase kernel wins from about 32 bytes per element, and
+//    likewise when the average is written back to all K replicas.
 static bool two_phase_possible(const cmn_plan *p) {
     return p->step_mode != STEP_ONE_PASS && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
 }
 bool prefer_two_phase_reduce(const cmn_plan *p) {
     return two_phase_possible(p) && (p->step_mode == STEP_TWO_PHASE || p->K >= 8);
 }
-bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem) {
+bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem, int mean_dest) {
     if (!two_phase_possible(p)) return false;
     if (p->step_mode == STEP_TWO_PHASE) return true;
     const bool cached = double(p->N) * state_bytes_per_elem <= 256.0 * 1024.0 * 1024.0;
-    return p->K * elem_bytes(p->dtype) >= (cached ? 56 : 32);
+    const bool light_stores = cached && mean_dest != CMN_MEAN_TO_ALL_REPLICAS;
+    return p->K * elem_bytes(p->dtype) >= (light_stores ? 56 : 32);
 }
 
 int check_launch(const cmn_plan *p) {
@@ -236,8 +238,8 @@ int64_t cmn_plan_total_elems(const cmn_plan *p) { return p ? p->N : -1; }
 int64_t cmn_plan_padded_elems(const cmn_plan *p) { return p ? p->L : -1; }
 int64_t cmn_plan_chunk_elems(const cmn_plan *p) { return p ? p->chunk_elems : -1; }
 int64_t cmn_plan_tile_count(const cmn_plan *p) { return p ? p->n_tiles : -1; }
-int cmn_plan_step_kernel_kind(const cmn_plan *p, int adam) {
-    return p ? (prefer_two_phase_step(p, adam ? 12 : 8) ? 2 : 1) : -1;
+int cmn_plan_step_kernel_kind(const cmn_plan *p, int adam, int mean_dest) {
+    return p ? (prefer_two_phase_step(p, adam ? 12 : 8, mean_dest) ? 2 : 1) : -1;
 }
 size_t cmn_plan_workspace_bytes(const cmn_plan *p) { return p ? p->ws.total : 0; }
 

@@ -92,7 +92,8 @@ int check_launch(const cmn_plan *p);
 // CMN_STEP_KERNEL=stream in the environment forces the one-pass kernels (A/B runs, tests).
 int device_compute_units();
 bool prefer_two_phase_reduce(const cmn_plan *p);
-bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem);   // 8: p + velocity, 12: p + both Adam moments
+bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem /* 8: p + velocity, 12: p + both Adam moments */,
+                           int mean_dest);
 int64_t two_phase_grid(const cmn_plan *p);
 
 template <typename T>

@@ -322,7 +322,7 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool two_phase = prefer_two_phase_step(plan, OPT == OPT_ADAM ? 12 : 8);
+    const bool two_phase = prefer_two_phase_step(plan, OPT == OPT_ADAM ? 12 : 8, mean_dest);
     // One launch of the two-phase kernel covers at most one round of the persistent grid: a
     // kernel boundary realigns the workgroups' phases, which rounds drifting inside one launch
     // would lose (VGG-16, 5.3 rounds: 1931 us in one launch, 1830 us in six).  The tiles are

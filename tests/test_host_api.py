@@ -200,6 +200,10 @@ def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     assert [kind(big, K, "bf16") for K in (8, 15, 16)] == [1, 1, 2]
     adam = lambda numel, K, dt="f32": B.Plan(numel, K, K, 256, dt).adam_step_kernel_kind
     assert [adam(small, K) for K in (4, 7, 8, 32)] == [1, 1, 2, 2]     # both moments: 306 MB, beyond the cache
+    def to_all(K):
+        p = B.Plan(small, K, K)
+        return B.cmn_plan_step_kernel_kind(p.h, 0, B.CMN_MEAN_TO_ALL_REPLICAS)
+    assert [to_all(K) for K in (7, 8)] == [1, 2]                       # heavy stores: like state beyond the cache
     assert kind(small, 128, "i8s") == 1
     assert B.cmn_plan_step_kernel_kind(None) == -1
     monkeypatch.setenv("CMN_STEP_KERNEL", "two_phase")
