@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--grad-dtype", default=None, choices=("f32", "f16", "bf16", "i8s"),
                     help="override the gradient storage type of the workload (i8s: random int8 + scales)")
     ap.add_argument("--opt", default="sgd", choices=("sgd", "adam"), help="optimizer fused into the step")
+    ap.add_argument("--buckets", type=int, default=1,
+                    help="step the list as this many layer groups of about equal size, last group first "
+                         "(cmn_allreduce_step_range per group) instead of one call")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -140,6 +143,24 @@ def main():
             plan.allreduce_adam_step(1e-3, 0.9, 0.999, 1e-8, c.wd, it[0], mean_dest=args.mean_dest)
     else:
         step = lambda: plan.allreduce_step(c.lr, c.mu, c.wd, mean_dest=args.mean_dest)
+    if args.buckets > 1:                            # layer groups of about N / buckets elements, back to front
+        edges, acc = [0], 0
+        for t, n in enumerate(c.numel):
+            acc += n
+            if acc >= c.N * len(edges) / args.buckets and len(edges) < args.buckets:
+                edges.append(t + 1)
+        edges.append(len(c.numel))
+        groups = [(a, b) for a, b in zip(edges[:-1], edges[1:]) if b > a][::-1]
+        log(f"[bench] {len(groups)} layer groups, stepped last group first")
+        if args.opt == "adam":
+            def step():
+                it[0] += 1
+                for a, b in groups:
+                    plan.allreduce_adam_step_range(a, b, 1e-3, 0.9, 0.999, 1e-8, c.wd, it[0], mean_dest=args.mean_dest)
+        else:
+            def step():
+                for a, b in groups:
+                    plan.allreduce_step_range(a, b, c.lr, c.mu, c.wd, mean_dest=args.mean_dest)
     torch.cuda.synchronize()
 
     per, span_ms, wall_ms = time_launches(torch, step, args.steps, args.warmup)
@@ -196,7 +217,7 @@ def main():
                "us_per_step": round(dt * 1e6, 1)}
         log(f"[bench] CPU oracle: {dt:.2f} s/step on {threads} threads -> {cpu['value']} GB/s effective")
 
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.config) if (args.opt, args.mean_dest) == ("sgd", 0) else None
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.config) if (args.opt, args.mean_dest, args.buckets) == ("sgd", 0, 1) else None
     out = {
         "metric": "effective HBM GB/s + \u00b5s per ResNet-50 allreduce+update step at K=32" if args.config == 3
                   else f"effective HBM GB/s + us per allreduce+update step ({c.name})",
@@ -205,7 +226,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": c.name, "tensors": len(c.tensors), "elements": c.N, "replicas_K": c.K,
                    "ring_chunks": c.n_chunks, "grad_storage": c.grad_dtype, "mean_dest": args.mean_dest,
-                   "optimizer": args.opt,
+                   "optimizer": args.opt, "layer_groups": args.buckets,
                    "entry": "cmn_allreduce_adam_step" if args.opt == "adam" else "cmn_allreduce_step"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,

@@ -23,6 +23,9 @@ constexpr int kStashFloats = 200;
 
 enum { STEP_AUTO = 0, STEP_ONE_PASS = 1, STEP_TWO_PHASE = 2 };
 
+// Fewer tiles than this in one launch of the fused step: the one-pass kernel, whatever the plan-wide choice.
+constexpr int64_t kMinTwoPhaseTiles = 4096;
+
 // What the tensor-space kernels read per tile: the fields of the public cmn_tile plus the tile's
 // own addresses, so that one 64-byte scalar load yields everything but the gradient pointers
 // (looking p, state and mean gradient up by tensor index would put three more dependent scalar

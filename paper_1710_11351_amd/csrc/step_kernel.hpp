@@ -322,7 +322,12 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool two_phase = prefer_two_phase_step(plan, OPT == OPT_ADAM ? 12 : 8, mean_dest);
+    // A launch of the persistent kernel costs about 8 us more than one of the one-pass kernel (its
+    // workgroups start and drain together) and repays that only over a few thousand tiles: small
+    // layer groups of a bucketed step take the one-pass kernel (ResNet-50, K = 32, 16 groups:
+    // 739 -> 651 us per step).
+    const bool two_phase = prefer_two_phase_step(plan, OPT == OPT_ADAM ? 12 : 8, mean_dest) &&
+                           (n >= kMinTwoPhaseTiles || plan->step_mode == STEP_TWO_PHASE);
     // One launch of the two-phase kernel covers at most one round of the persistent grid: a
     // kernel boundary realigns the workgroups' phases, which rounds drifting inside one launch
     // would lose (VGG-16, 5.3 rounds: 1931 us in one launch, 1830 us in six).  The tiles are
