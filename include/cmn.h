@@ -120,7 +120,8 @@ size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_
 /* Which kernel kind the fused step launches for this plan with MomentumSGD (adam == 0) or Adam
  * (adam != 0) and the given cmn_mean_dest: a tuning decision that never changes results; for
  * benchmarks and profiles.  1 = one pass, a workgroup per tile; 2 = persistent grid that reads
- * first and writes afterwards; -1 if plan is NULL. */
+ * first and writes afterwards (a _range call over a small layer group still uses kind 1);
+ * -1 if plan is NULL. */
 int cmn_plan_step_kernel_kind(const cmn_plan *plan, int adam, int mean_dest);
 
 /* Pure host: compute the work-unit table that cmn_plan_bind would upload for these
