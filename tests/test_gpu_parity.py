@@ -74,6 +74,31 @@ def test_streams_without_a_common_alignment(K, dtype, opt, mis):
     run_parity(c, steps=2, misalign=mis, opt=opt)
 
 
+def _random_case(seed):
+    rng = np.random.default_rng(seed)
+    sizes = [0, 1, 3, 7, 8, 63, 64, 1000, 1023, 1024, 1025, 2047, 2048, 2049, 4095, 4096, 4097, 5000, 12345, 40000]
+    numel = [int(rng.choice(sizes)) for _ in range(int(rng.integers(1, 10)))]
+    if sum(numel) == 0:
+        numel.append(777)
+    dtype = str(rng.choice(["f32", "f32", "f16", "bf16"]))
+    mis = int(rng.integers(0, 4))
+    misalign = mis if rng.random() < 0.7 else tuple(int(x) for x in rng.integers(0, 4, size=4))
+    return dict(numel=numel, K=int(rng.integers(1, 21)), C=int(rng.integers(1, 10)), dtype=dtype, misalign=misalign,
+                opt=str(rng.choice(["sgd", "adam"])), rot=int(rng.integers(0, 2)), wd=float(rng.choice([0.0, 1e-3])),
+                bucketed=bool(rng.random() < 0.3))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_lists_replica_counts_and_alignments(seed):
+    """Seeded random workloads: list shapes around the tile sizes, 1..20 replicas, 1..9 ring chunks,
+    every storage type, common and conflicting misalignments, both optimizers, both fold orders."""
+    k = _random_case(seed)
+    c = wl.custom_config(k["numel"], K=k["K"], n_chunks=k["C"], grad_dtype=k["dtype"], cfg=60 + seed, wd=k["wd"],
+                         outlier_frac=0.01 if k["dtype"] == "f16" else 0.0)
+    run_parity(c, steps=2, ring_rotate=k["rot"], misalign=k["misalign"], opt=k["opt"], staged=not k["bucketed"],
+               bucketed=k["bucketed"])
+
+
 def test_single_replica_is_the_plain_optimizer():
     c = wl.custom_config([3000, 100], K=1, n_chunks=1, cfg=93)
     run_parity(c, steps=2)
