@@ -80,7 +80,7 @@ def _random_case(seed):
     numel = [int(rng.choice(sizes)) for _ in range(int(rng.integers(1, 10)))]
     if sum(numel) == 0:
         numel.append(777)
-    dtype = str(rng.choice(["f32", "f32", "f16", "bf16"]))
+    dtype = str(rng.choice(["f32", "f32", "f16", "bf16", "i8s"]))
     mis = int(rng.integers(0, 4))
     misalign = mis if rng.random() < 0.7 else tuple(int(x) for x in rng.integers(0, 4, size=4))
     return dict(numel=numel, K=int(rng.integers(1, 21)), C=int(rng.integers(1, 10)), dtype=dtype, misalign=misalign,
@@ -88,7 +88,7 @@ def _random_case(seed):
                 bucketed=bool(rng.random() < 0.3))
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(20))
 def test_random_lists_replica_counts_and_alignments(seed):
     """Seeded random workloads: list shapes around the tile sizes, 1..20 replicas, 1..9 ring chunks,
     every storage type, common and conflicting misalignments, both optimizers, both fold orders."""
