@@ -130,7 +130,9 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
         if (!plan->bound || !plan->have_scales) return CMN_EUNBOUND;
         scales = ws_ptr<const float *const>(plan, plan->ws.scale_ptrs);
     }
-    if (prefer_two_phase_reduce(plan) && kReduceIters == 1) {
+    // (a launch of the persistent kernel only pays off over a few thousand tiles)
+    if (prefer_two_phase_reduce(plan) && kReduceIters == 1 &&
+        (tpc * plan->C >= kMinTwoPhaseTiles || plan->step_mode == STEP_TWO_PHASE)) {
         // one launch per round of the persistent grid, tiles spread evenly (a kernel boundary
         // realigns the phases of the workgroups)
         const long long n_tiles = tpc * plan->C, resident = two_phase_grid(plan);
