@@ -321,6 +321,7 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     }
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
+    if (n > 0x7fffffffLL) return CMN_ESIZE;            // one workgroup per tile must fit a grid
     hipStream_t s = static_cast<hipStream_t>(stream);
     // A launch of the persistent kernel costs about 8 us more than one of the one-pass kernel (its
     // workgroups start and drain together) and repays that only over a few thousand tiles: small
@@ -368,6 +369,7 @@ inline int launch_optimizer(const cmn_plan *plan, const OptArgs &o, void *stream
     if (!plan->have_opt || !plan->have_mean) return CMN_EUNBOUND;
     if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
     if (plan->n_tiles == 0) return CMN_OK;
+    if (plan->n_tiles > 0x7fffffffLL) return CMN_ESIZE;
     launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
     return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
 }

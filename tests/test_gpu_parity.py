@@ -336,6 +336,56 @@ def test_config5_vgg16_k16_adam_staged_full_size():
     run_parity(wl.config(5), steps=1, opt="adam", fused=False)
 
 
+def test_more_than_2_to_31_elements_full_size(monkeypatch):
+    """One tensor of 2^31 + 5000 binary16 elements (offsets beyond 32 bits in every kernel), two replicas.
+    The oracle cannot hold this, so the check is against the same arithmetic written with torch's
+    elementwise fp32 operations, each of which rounds once: (g0 + g1) * 0.5, mu*v - lr*g, p + v."""
+    import torch
+    from paper_1710_11351_amd import binding as B
+    n = (1 << 31) + 5000
+    numel = [777, n, 3]
+    gen = torch.Generator(device="cuda").manual_seed(4242)
+    def rnd(m, dt, std):
+        out = torch.empty(m, dtype=dt, device="cuda")
+        for a in range(0, m, 1 << 28):                      # generated piecewise to bound the temporaries
+            b = min(m, a + (1 << 28))
+            out[a:b] = (torch.randn(b - a, device="cuda", generator=gen) * std).to(dt)
+        return out
+    g = [[rnd(m, torch.float16, 1e-2) for m in numel] for _ in range(2)]
+    p = [rnd(m, torch.float32, 0.05) for m in numel]
+    v = [rnd(m, torch.float32, 0.01) for m in numel]
+    m_fused = [torch.empty(m, dtype=torch.float32, device="cuda") for m in numel]
+    lr, mu = 0.1, 0.9
+    want_p, want_v, want_m = [], [], []
+    for t in range(len(numel)):
+        mean = (g[0][t].float() + g[1][t].float()) * 0.5
+        nv = mu * v[t] - lr * mean
+        want_m.append(mean); want_v.append(nv); want_p.append(p[t] + nv)
+    plan = B.Plan(numel, 2, 2, 256, "f16")
+    # staged entry points first (they leave p and v untouched until cmn_momentum_sgd, which is skipped)
+    plan.bind(g, p, v, m_fused)
+    packed = torch.empty(2 * plan.L, dtype=torch.float16, device="cuda")
+    reduced = torch.empty(plan.L, dtype=torch.float32, device="cuda")
+    plan.pack(packed); plan.ring_reduce(packed, reduced); plan.scale_unpack(reduced)
+    torch.cuda.synchronize()
+    for t in range(len(numel)):
+        assert torch.equal(m_fused[t].view(torch.int32), want_m[t].view(torch.int32)), f"staged mean, tensor {t}"
+        m_fused[t].zero_()
+    del packed, reduced, plan
+    p0, v0 = [x.clone() for x in p], [x.clone() for x in v]
+    for mode in ("stream", "two_phase"):                       # both fused kernels, whatever the library would pick
+        monkeypatch.setenv("CMN_STEP_KERNEL", mode)
+        plan = B.Plan(numel, 2, 2, 256, "f16")
+        for t in range(len(numel)):
+            p[t].copy_(p0[t]); v[t].copy_(v0[t]); m_fused[t].zero_()
+        plan.bind(g, p, v, m_fused)
+        plan.allreduce_step(lr, mu, 0.0, write_mean_grad=True)
+        torch.cuda.synchronize()
+        for t in range(len(numel)):
+            for name, a, b in (("mean", m_fused, want_m), ("v", v, want_v), ("p", p, want_p)):
+                assert torch.equal(a[t].view(torch.int32), b[t].view(torch.int32)), f"{mode} {name}, tensor {t}"
+
+
 def test_f16_storage_within_2e3_of_unquantised_fp32():
     """Config 4's value distribution (1 % of elements at 100x) on a smaller list: the mean gradient
     from fp16-stored gradients stays within 2e-3 of the float64 mean b of the un-quantised fp32
