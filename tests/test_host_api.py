@@ -288,3 +288,36 @@ def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis, i
             else:        # no head makes all streams 16-byte aligned at once
                 assert not any(all((addr + (e0 + hh) * es) % 16 == 0 for addr, es in lst(t)) for hh in range(w))
     assert covered == list(numel)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU program: asking for more exits with a message, before any GPU work."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, env=env)
+    assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
+
+
+def test_algorithmic_bytes_match_the_stated_formulas():
+    """bench.py prices a launch at (K*e_g + 16)*N bytes (+4N with the mean stored, +K*e_g*N handed back to all
+    replicas, +8N for Adam's second moment) and the staged entry points at 2*K*e_g*N, (K*e_g+4)*N, 8N, 20N."""
+    import importlib.util
+    from paper_1710_11351_amd import workloads as wl
+    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    c = wl.config(3)
+    N, K = c.N, c.K
+    assert bench.algorithmic_bytes(c, "step", 0, "sgd") == (4 * K + 16) * N == 3_680_212_608
+    assert bench.algorithmic_bytes(c, "step", 1, "sgd") == (4 * K + 20) * N
+    assert bench.algorithmic_bytes(c, "step", 2, "sgd") == (8 * K + 16) * N
+    assert bench.algorithmic_bytes(c, "step", 0, "adam") == (4 * K + 24) * N
+    assert bench.algorithmic_bytes(c, "pack") == 2 * K * 4 * N
+    assert bench.algorithmic_bytes(c, "ring_reduce") == (4 * K + 4) * N
+    assert bench.algorithmic_bytes(c, "scale_unpack") == 8 * N
+    assert bench.algorithmic_bytes(c, "momentum_sgd") == 20 * N
+    c4 = wl.config(4)
+    assert bench.algorithmic_bytes(c4, "step", 0, "sgd") == (2 * 128 + 16) * c4.N
