@@ -100,10 +100,15 @@ typedef struct cmn_tile {
     int8_t head[8];
 } cmn_tile;
 
-/* Create a plan for `n_tensors` tensors of numel[t] >= 0 elements (host array, copied),
+/* The plan object, its chunk geometry and its tables are not in the paper: they are this build's
+ * way of fixing the summation order and of finding K*T scattered tensors from a kernel.
+ * Create a plan for `n_tensors` tensors of numel[t] >= 0 elements (host array, copied),
  * K >= 1 replicas, n_chunks >= 1 ring chunks, align_bytes a power of two that is a
  * multiple of 16 (256 in every published workload), grad_dtype a cmn_dtype, and
  * ring_rotate 0 or 1.  n_tensors may be 0 and tensors may be empty.  Pure host work.
+ * Two environment variables are read here (launch shape only, results never change):
+ * CMN_STEP_KERNEL=stream | two_phase forces the one-pass / the persistent two-phase kernels
+ * wherever that kind exists, and CMN_TWO_PHASE_GRID=n caps the persistent grid at n workgroups.
  * Errors: CMN_ENULL (out, or numel with n_tensors > 0), CMN_EINVAL, CMN_ESIZE
  * (n_tensors or K above the supported maximum, or sizes that overflow), CMN_ENOMEM. */
 int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel /* host [T] */, int K,
@@ -118,11 +123,13 @@ int64_t cmn_plan_chunk_elems(const cmn_plan *plan);  /* roundup(ceil(N / n_chunk
 int64_t cmn_plan_tile_count(const cmn_plan *plan);   /* number of cmn_tile work units             */
 size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_bind needs (>= 256) */
 /* Which kernel kind the fused step launches for this plan with MomentumSGD (adam == 0) or Adam
- * (adam != 0) and the given cmn_mean_dest: a tuning decision that never changes results; for
- * benchmarks and profiles.  1 = one pass, a workgroup per tile; 2 = persistent grid that reads
- * first and writes afterwards (a _range call over a small layer group still uses kind 1);
- * -1 if plan is NULL. */
+ * (adam != 0) and the given cmn_mean_dest, over the whole list or over tensors
+ * [tensor_begin, tensor_end): a tuning decision that never changes results; for benchmarks and
+ * profiles.  1 = one pass, a workgroup per tile; 2 = persistent grid that reads first and
+ * writes afterwards (small lists and layer groups use kind 1); -1 if plan is NULL or the range
+ * is not inside the list. */
 int cmn_plan_step_kernel_kind(const cmn_plan *plan, int adam, int mean_dest);
+int cmn_plan_range_kernel_kind(const cmn_plan *plan, int tensor_begin, int tensor_end, int adam, int mean_dest);
 
 /* Pure host: compute the work-unit table that cmn_plan_bind would upload for these
  * pointer arrays (same meaning as in cmn_plan_bind; addresses are only inspected,
@@ -142,26 +149,34 @@ int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, 
  * CMN_EUNBOUND: cmn_pack needs gradients, cmn_scale_unpack mean gradients,
  * cmn_momentum_sgd mean gradients + parameters + velocities, cmn_allreduce_step gradients
  * + parameters + velocities (+ mean gradients if asked to write them).  Pointers of empty
- * tensors are ignored.  The call waits for `stream` before it returns.  May be
- * repeated to rebind.  Errors: CMN_ENULL, CMN_EALIGN, CMN_EHIP. */
+ * tensors are ignored.  The call waits for `stream` before it returns (set-up, not the hot
+ * path: its tables travel from pageable host memory).  May be repeated to rebind; every bind
+ * starts afresh, so Adam's second moments (cmn_plan_bind_adam) and int8 scales
+ * (cmn_plan_bind_scales) of an earlier binding are dropped and must be bound again.
+ * Errors: CMN_ENULL, CMN_EALIGN, CMN_EHIP. */
 int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_ptrs /* host [K*T] */,
                   void *const *param_ptrs /* host [T] */, void *const *vel_ptrs /* host [T] */,
                   void *const *mean_grad_ptrs /* host [T] or NULL */, void *stream);
 
-/* S1 pack.  For every replica k copy its T gradient tensors in list order, with no
- * gaps, to packed[k*L .. k*L + N) and write zeros to packed[k*L + N .. (k+1)*L).
+/* S1 pack.  Not in the paper, which only says that gradients exist per parameter tensor
+ * (Section 2.1) and are exchanged by Allreduce (Section 2.3); the contiguous buffer and its
+ * chunking are this build's design.  For every replica k copy its T gradient tensors in list
+ * order, with no gaps, to packed[k*L .. k*L + N) and write zeros to packed[k*L + N .. (k+1)*L).
  * packed: device, K*L elements of grad_dtype, 256-byte aligned.  Bit copy. */
 int cmn_pack(const cmn_plan *plan, void *packed /* device [K][L] */, void *stream);
 
-/* S2 ring-order reduction.  reduced[i] = fixed-order float32 sum over k of packed[k][i]
- * (order defined at the top of this file).  packed as written by cmn_pack; reduced:
- * device, L float32, 256-byte aligned, must not overlap packed.  Needs no bound tensors
- * (but the plan must have been bound, for a uniform rule). */
+/* S2 ring-order reduction (the arithmetic share of the paper's Allreduce step, Section 2.3; the
+ * ring order is this build's reading, see the top of this file).  reduced[i] = fixed-order
+ * float32 sum over k of packed[k][i].  packed as written by cmn_pack; reduced: device, L float32,
+ * 256-byte aligned, must not overlap packed.  Works on the two buffers alone: the plan need not
+ * be bound (only a CMN_I8S plan must be, with scales: CMN_EUNBOUND otherwise). */
 int cmn_ring_reduce(const cmn_plan *plan, const void *packed /* device [K][L] */,
                     float *reduced /* device [L] */, void *stream);
 
-/* S3 + S4 scale and unpack.  mean_grad[t][e] = reduced[off[t] + e] * (1.0f / (float)K)
- * for every tensor; padding is dropped.  Needs mean_grad_ptrs bound. */
+/* S3 + S4 scale and unpack: the sum becomes the average that Section 2.3 says every worker
+ * obtains; how it is laid out is not in the paper (this build's design, like cmn_pack).
+ * mean_grad[t][e] = reduced[off[t] + e] * (1.0f / (float)K) for every tensor; padding is
+ * dropped.  Needs mean_grad_ptrs bound. */
 int cmn_scale_unpack(const cmn_plan *plan, const float *reduced /* device [L] */, void *stream);
 
 /* S5 MomentumSGD on every element, reading the bound mean gradients g:

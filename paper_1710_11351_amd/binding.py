@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         getattr(L, name).argtypes = [vp]
     L.cmn_plan_step_kernel_kind.restype = ctypes.c_int
     L.cmn_plan_step_kernel_kind.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    L.cmn_plan_range_kernel_kind.restype = ctypes.c_int
+    L.cmn_plan_range_kernel_kind.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     L.cmn_plan_workspace_bytes.restype = ctypes.c_size_t
     L.cmn_plan_workspace_bytes.argtypes = [vp]
     L.cmn_plan_describe_tiles.restype = ctypes.c_int
@@ -168,6 +170,10 @@ def cmn_plan_tile_count(h) -> int:
 
 def cmn_plan_step_kernel_kind(h, adam: int = 0, mean_dest: int = 0) -> int:
     return lib().cmn_plan_step_kernel_kind(h, int(adam), int(mean_dest))
+
+
+def cmn_plan_range_kernel_kind(h, tensor_begin: int, tensor_end: int, adam: int = 0, mean_dest: int = 0) -> int:
+    return lib().cmn_plan_range_kernel_kind(h, int(tensor_begin), int(tensor_end), int(adam), int(mean_dest))
 
 
 def cmn_plan_workspace_bytes(h) -> int:

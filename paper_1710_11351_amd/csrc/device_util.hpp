@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <tuple>
+#include <utility>
 
 #include "../../include/cmn.h"
 #include "plan.hpp"
@@ -14,6 +16,23 @@
 #pragma clang fp contract(off)
 
 namespace cmn {
+
+// Kernel launch that hands back the launch's own status.  (The <<<>>> form reports failures only
+// through the runtime's sticky last-error slot, which may hold an error of the caller's earlier
+// HIP calls and which reading would clear.)  Arguments are converted to the kernel's exact
+// parameter types first, since the runtime copies them by address.
+template <typename... P, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kernel)(P...), dim3 grid, dim3 block, size_t shm, hipStream_t s,
+                                     std::tuple<P...> &vals, std::index_sequence<I...>) {
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))..., nullptr};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, shm, s);
+}
+template <typename... P, typename... A>
+inline hipError_t launch_kernel(void (*kernel)(P...), dim3 grid, dim3 block, size_t shm, hipStream_t s, A &&...a) {
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    std::tuple<P...> vals{static_cast<P>(std::forward<A>(a))...};
+    return launch_kernel_impl(kernel, grid, block, shm, s, vals, std::index_sequence_for<P...>{});
+}
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -146,13 +146,14 @@ extern "C" int cmn_pack(const cmn_plan *plan, void *packed, void *stream) {
     const long long *off = ws_ptr<const long long>(plan, plan->ws.off_table);
     const void *const *rows = ws_ptr<const void *const>(plan, plan->ws.grad_rows);
     const long long N = plan->N, L = plan->L;
+    hipError_t err;
 #define CMN_LAUNCH_PACK(DT, LDS) \
-    hipLaunchKernelGGL((k_pack<DT, LDS>), grid, dim3(kBlock), shm, s, off, rows, packed, T, N, L)
+    err = launch_kernel(k_pack<DT, LDS>, grid, dim3(kBlock), shm, s, off, rows, packed, T, N, L)
     if (plan->dtype == CMN_F32) { if (lds) CMN_LAUNCH_PACK(CMN_F32, true); else CMN_LAUNCH_PACK(CMN_F32, false); }
     else if (plan->dtype == CMN_I8S) { if (lds) CMN_LAUNCH_PACK(CMN_I8S, true); else CMN_LAUNCH_PACK(CMN_I8S, false); }
     else /* any 16-bit type: a bit copy */ { if (lds) CMN_LAUNCH_PACK(CMN_F16, true); else CMN_LAUNCH_PACK(CMN_F16, false); }
 #undef CMN_LAUNCH_PACK
-    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+    return err == hipSuccess ? CMN_OK : CMN_EHIP;
 }
 
 extern "C" int cmn_scale_unpack(const cmn_plan *plan, const float *reduced, void *stream) {
@@ -172,11 +173,12 @@ extern "C" int cmn_scale_unpack(const cmn_plan *plan, const float *reduced, void
     float *const *mean = ws_ptr<float *const>(plan, plan->ws.mean_ptrs);
     const float inv_k = 1.0f / float(plan->K);
     const bool big = beyond_cache(4.0 * double(plan->N));
+    hipError_t err;
 #define CMN_LAUNCH_UNPACK(LDS, STREAM)                                                                       \
-    hipLaunchKernelGGL((k_scale_unpack<LDS, STREAM>), dim3(unsigned(nx)), dim3(kBlock), shm, s, off, mean, reduced, T, \
-                       (long long)plan->N, inv_k)
+    err = launch_kernel(k_scale_unpack<LDS, STREAM>, dim3(unsigned(nx)), dim3(kBlock), shm, s, off, mean, reduced, T, \
+                        (long long)plan->N, inv_k)
     if (lds) { if (big) CMN_LAUNCH_UNPACK(true, true); else CMN_LAUNCH_UNPACK(true, false); }
     else { if (big) CMN_LAUNCH_UNPACK(false, true); else CMN_LAUNCH_UNPACK(false, false); }
 #undef CMN_LAUNCH_UNPACK
-    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+    return err == hipSuccess ? CMN_OK : CMN_EHIP;
 }

@@ -161,6 +161,68 @@ bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem, int mean
     return p->K * elem_bytes(p->dtype) >= (light_stores ? 56 : 32);
 }
 
+int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows, unsigned elem_bytes) {
+    for (int r = 0; r < rows; ++r)
+        for (int t = 0; t < p->T; ++t) {
+            if (p->numel[t] == 0) continue;
+            const void *q = ptrs[size_t(r) * p->T + t];
+            if (!q) return CMN_ENULL;
+            if (reinterpret_cast<uintptr_t>(q) % elem_bytes) return CMN_EALIGN;
+        }
+    return CMN_OK;
+}
+
+// Rebuild the tile table inside a table image from the pointer tables the image holds.
+static void fill_tile_table(const cmn_plan *p, unsigned char *img, const BoundLists &have) {
+    auto tab = [&](size_t off) { return reinterpret_cast<void *const *>(img + off); };
+    const void *const *gp = have.grads ? reinterpret_cast<const void *const *>(img + p->ws.grad_rows) : nullptr;
+    void *const *pp = have.opt ? tab(p->ws.param_ptrs) : nullptr, *const *vp = have.opt ? tab(p->ws.vel_ptrs) : nullptr;
+    void *const *mp = have.mean ? tab(p->ws.mean_ptrs) : nullptr, *const *sp = have.state2 ? tab(p->ws.state2_ptrs) : nullptr;
+    std::vector<cmn_tile> table(size_t(p->n_tiles));
+    build_tiles(*p, gp, pp, vp, mp, sp, table.data());
+    DeviceTile *out = reinterpret_cast<DeviceTile *>(img + p->ws.tiles);
+    auto at = [](void *const *base, const cmn_tile &tl) {
+        return base ? static_cast<float *>(base[tl.tensor]) + tl.e0 : nullptr;
+    };
+    for (size_t i = 0; i < table.size(); ++i) {
+        const cmn_tile &tl = table[i];
+        DeviceTile &d = out[i];
+        d.p = at(pp, tl); d.s1 = at(vp, tl); d.s2 = at(sp, tl); d.m = at(mp, tl);
+        d.e0 = tl.e0; d.len = tl.len; d.tensor = tl.tensor; d.start_rank = tl.start_rank; d.chunk = tl.chunk;
+        std::memcpy(d.head, tl.head, sizeof d.head);
+    }
+}
+
+void fill_table_image(const cmn_plan *p, unsigned char *img, const void *const *grad_ptrs, void *const *param_ptrs,
+                      void *const *vel_ptrs, void *const *mean_ptrs, void *const *state2_ptrs,
+                      const float *const *scale_ptrs) {
+    std::memset(img, 0, p->ws.total);
+    std::memcpy(img + p->ws.off_table, p->off.data(), sizeof(int64_t) * (size_t(p->T) + 1));
+    const size_t T = size_t(p->T), K = size_t(p->K);
+    if (grad_ptrs) {
+        auto **rows = reinterpret_cast<const void **>(img + p->ws.grad_rows);
+        auto **cols = reinterpret_cast<const void **>(img + p->ws.grad_cols);
+        for (size_t k = 0; k < K; ++k)
+            for (size_t t = 0; t < T; ++t) {
+                rows[k * T + t] = grad_ptrs[k * T + t];
+                cols[t * K + k] = grad_ptrs[k * T + t];
+            }
+    }
+    if (param_ptrs) std::memcpy(img + p->ws.param_ptrs, param_ptrs, sizeof(void *) * T);
+    if (vel_ptrs) std::memcpy(img + p->ws.vel_ptrs, vel_ptrs, sizeof(void *) * T);
+    if (mean_ptrs) std::memcpy(img + p->ws.mean_ptrs, mean_ptrs, sizeof(void *) * T);
+    if (state2_ptrs) std::memcpy(img + p->ws.state2_ptrs, state2_ptrs, sizeof(void *) * T);
+    if (scale_ptrs) std::memcpy(img + p->ws.scale_ptrs, scale_ptrs, sizeof(void *) * K);
+    fill_tile_table(p, img, BoundLists{grad_ptrs != nullptr, param_ptrs && vel_ptrs, mean_ptrs != nullptr,
+                                       state2_ptrs != nullptr, scale_ptrs != nullptr});
+}
+
+int fused_range_kernel_kind(const cmn_plan *p, bool adam, int mean_dest, int64_t n_tiles) {
+    return prefer_two_phase_step(p, adam ? 12 : 8, mean_dest) &&
+                   (n_tiles >= kMinTwoPhaseTiles || p->step_mode == STEP_TWO_PHASE)
+               ? 2 : 1;
+}
+
 int check_launch(const cmn_plan *p) {
     if (!p) return CMN_ENULL;
     if (!p->bound) return CMN_EUNBOUND;
@@ -206,12 +268,7 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
     p->L = p->chunk_elems * n_chunks;
     if (p->L > kMaxElems || p->L * K > (int64_t(1) << 50)) { delete p; return CMN_ESIZE; }
 
-    int iters = kTileIters;
-    if (const char *s = std::getenv("CMN_TILE_ITERS")) {  // tuning knob for experiments
-        const int v = std::atoi(s);
-        if (v >= 1 && v <= 64) iters = v;
-    }
-    p->tile_elems = kBlock * vec_elems(grad_dtype) * iters;
+    p->tile_elems = kBlock * vec_elems(grad_dtype) * kTileIters;
     if (const char *k = std::getenv("CMN_STEP_KERNEL"))
         p->step_mode = std::strcmp(k, "stream") == 0 ? STEP_ONE_PASS : std::strcmp(k, "two_phase") == 0 ? STEP_TWO_PHASE : STEP_AUTO;
     if (const char *k = std::getenv("CMN_TWO_PHASE_GRID")) p->grid_limit = std::atoi(k) > 0 ? std::atoi(k) : 0;
@@ -239,20 +296,14 @@ int64_t cmn_plan_padded_elems(const cmn_plan *p) { return p ? p->L : -1; }
 int64_t cmn_plan_chunk_elems(const cmn_plan *p) { return p ? p->chunk_elems : -1; }
 int64_t cmn_plan_tile_count(const cmn_plan *p) { return p ? p->n_tiles : -1; }
 int cmn_plan_step_kernel_kind(const cmn_plan *p, int adam, int mean_dest) {
-    return p ? (prefer_two_phase_step(p, adam ? 12 : 8, mean_dest) ? 2 : 1) : -1;
+    return p ? fused_range_kernel_kind(p, adam != 0, mean_dest, p->n_tiles) : -1;
+}
+int cmn_plan_range_kernel_kind(const cmn_plan *p, int tensor_begin, int tensor_end, int adam, int mean_dest) {
+    if (!p || tensor_begin < 0 || tensor_end < tensor_begin || tensor_end > p->T) return -1;
+    return fused_range_kernel_kind(p, adam != 0, mean_dest,
+                                   p->first_tile[size_t(tensor_end)] - p->first_tile[size_t(tensor_begin)]);
 }
 size_t cmn_plan_workspace_bytes(const cmn_plan *p) { return p ? p->ws.total : 0; }
-
-static int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows, unsigned elem_bytes) {
-    for (int r = 0; r < rows; ++r)
-        for (int t = 0; t < p->T; ++t) {
-            if (p->numel[t] == 0) continue;
-            const void *q = ptrs[size_t(r) * p->T + t];
-            if (!q) return CMN_ENULL;
-            if (reinterpret_cast<uintptr_t>(q) % elem_bytes) return CMN_EALIGN;
-        }
-    return CMN_OK;
-}
 
 int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, void *const *param_ptrs,
                             void *const *vel_ptrs, void *const *mean_grad_ptrs, void *const *second_moment_ptrs,
@@ -270,34 +321,10 @@ int cmn_plan_describe_tiles(const cmn_plan *plan, const void *const *grad_ptrs, 
     return CMN_OK;
 }
 
-// Rebuild the tile table inside the staging image from the pointer tables it holds and
-// copy the image to the device workspace.
+// Copy the staging image to the device workspace and wait for the copy: the image is pageable
+// host memory that the next bind call rewrites.
 static int upload_image(cmn_plan *p, void *dev_workspace, hipStream_t s) {
-    unsigned char *img = p->staging.data();
-    auto tab = [&](size_t off) { return reinterpret_cast<void *const *>(img + off); };
-    try {
-        std::vector<const void *> flat;
-        if (p->have_grads) {
-            flat.assign(reinterpret_cast<const void *const *>(img + p->ws.grad_rows),
-                        reinterpret_cast<const void *const *>(img + p->ws.grad_rows) + size_t(p->K) * p->T);
-        }
-        void *const *pp = p->have_opt ? tab(p->ws.param_ptrs) : nullptr, *const *vp = p->have_opt ? tab(p->ws.vel_ptrs) : nullptr;
-        void *const *mp = p->have_mean ? tab(p->ws.mean_ptrs) : nullptr, *const *sp = p->have_state2 ? tab(p->ws.state2_ptrs) : nullptr;
-        std::vector<cmn_tile> table(size_t(p->n_tiles));
-        build_tiles(*p, p->have_grads ? flat.data() : nullptr, pp, vp, mp, sp, table.data());
-        DeviceTile *out = reinterpret_cast<DeviceTile *>(img + p->ws.tiles);
-        auto at = [](void *const *base, const cmn_tile &tl) {
-            return base ? static_cast<float *>(base[tl.tensor]) + tl.e0 : nullptr;
-        };
-        for (size_t i = 0; i < table.size(); ++i) {
-            const cmn_tile &tl = table[i];
-            DeviceTile &d = out[i];
-            d.p = at(pp, tl); d.s1 = at(vp, tl); d.s2 = at(sp, tl); d.m = at(mp, tl);
-            d.e0 = tl.e0; d.len = tl.len; d.tensor = tl.tensor; d.start_rank = tl.start_rank; d.chunk = tl.chunk;
-            std::memcpy(d.head, tl.head, sizeof d.head);
-        }
-    } catch (...) { return CMN_ENOMEM; }
-    if (hipMemcpyAsync(dev_workspace, img, p->ws.total, hipMemcpyHostToDevice, s) != hipSuccess) return CMN_EHIP;
+    if (hipMemcpyAsync(dev_workspace, p->staging.data(), p->ws.total, hipMemcpyHostToDevice, s) != hipSuccess) return CMN_EHIP;
     if (hipStreamSynchronize(s) != hipSuccess) return CMN_EHIP;
     return CMN_OK;
 }
@@ -316,27 +343,13 @@ int cmn_plan_bind(cmn_plan *plan, void *dev_workspace, const void *const *grad_p
 
     p->bound = false;
     try {
-        p->staging.assign(p->ws.total, 0);
+        p->staging.resize(p->ws.total);
+        fill_table_image(p, p->staging.data(), grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, nullptr, nullptr);
     } catch (...) { return CMN_ENOMEM; }
-    unsigned char *img = p->staging.data();
-    std::memcpy(img + p->ws.off_table, p->off.data(), sizeof(int64_t) * (size_t(p->T) + 1));
-    const size_t T = size_t(p->T), K = size_t(p->K);
-    if (grad_ptrs) {
-        auto **rows = reinterpret_cast<const void **>(img + p->ws.grad_rows);
-        auto **cols = reinterpret_cast<const void **>(img + p->ws.grad_cols);
-        for (size_t k = 0; k < K; ++k)
-            for (size_t t = 0; t < T; ++t) {
-                rows[k * T + t] = grad_ptrs[k * T + t];
-                cols[t * K + k] = grad_ptrs[k * T + t];
-            }
-    }
-    if (param_ptrs) std::memcpy(img + p->ws.param_ptrs, param_ptrs, sizeof(void *) * T);
-    if (vel_ptrs) std::memcpy(img + p->ws.vel_ptrs, vel_ptrs, sizeof(void *) * T);
-    if (mean_grad_ptrs) std::memcpy(img + p->ws.mean_ptrs, mean_grad_ptrs, sizeof(void *) * T);
     p->have_grads = grad_ptrs != nullptr;
     p->have_opt = param_ptrs != nullptr;
     p->have_mean = mean_grad_ptrs != nullptr;
-    p->have_state2 = false;
+    p->have_state2 = false;          // a new binding starts without Adam moments and int8 scales
     p->have_scales = false;
     if (int rc2 = upload_image(p, dev_workspace, static_cast<hipStream_t>(stream))) return rc2;
     p->dev_ws = static_cast<char *>(dev_workspace);
@@ -351,6 +364,9 @@ int cmn_plan_bind_adam(cmn_plan *plan, void *const *second_moment_ptrs, void *st
     std::memcpy(plan->staging.data() + plan->ws.state2_ptrs, second_moment_ptrs, sizeof(void *) * size_t(plan->T));
     plan->have_state2 = true;
     plan->bound = false;
+    try {
+        fill_tile_table(plan, plan->staging.data(), bound_lists(plan));
+    } catch (...) { return CMN_ENOMEM; }
     if (int rc = upload_image(plan, plan->dev_ws, static_cast<hipStream_t>(stream))) return rc;
     plan->bound = true;
     return CMN_OK;

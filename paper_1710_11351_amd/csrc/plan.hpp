@@ -79,6 +79,7 @@ struct cmn_plan {
     bool bound = false, have_grads = false, have_opt = false, have_mean = false, have_state2 = false, have_scales = false;
     char *dev_ws = nullptr;
     std::vector<unsigned char> staging;  // host image of the workspace
+
 };
 
 namespace cmn {
@@ -99,9 +100,34 @@ bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem /* 8: p +
                            int mean_dest);
 int64_t two_phase_grid(const cmn_plan *p);
 
+// 1 (one pass) or 2 (two-phase) for a fused-step launch over n_tiles tiles of this plan.
+int fused_range_kernel_kind(const cmn_plan *p, bool adam, int mean_dest, int64_t n_tiles);
+
+// Which tensor lists a table image holds.
+struct BoundLists {
+    bool grads, opt, mean, state2, scales;
+};
+inline BoundLists bound_lists(const cmn_plan *p) {
+    return BoundLists{p->have_grads, p->have_opt, p->have_mean, p->have_state2, p->have_scales};
+}
+
+// Writes the plan's tables for these pointer arrays (each may be null) into img[0 .. ws.total):
+// offsets, both gradient pointer tables, the [T] pointer tables, the scale pointers and the
+// tile table.  Pure host work; throws std::bad_alloc only.
+void fill_table_image(const cmn_plan *p, unsigned char *img, const void *const *grad_ptrs, void *const *param_ptrs,
+                      void *const *vel_ptrs, void *const *mean_ptrs, void *const *state2_ptrs,
+                      const float *const *scale_ptrs);
+
+// Null / alignment check of a pointer array with `rows` rows of T entries (entries of empty tensors are ignored).
+int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows, unsigned elem_bytes);
+
+template <typename T>
+inline T *ws_ptr(const char *ws, size_t byte_off) {
+    return reinterpret_cast<T *>(const_cast<char *>(ws) + byte_off);
+}
 template <typename T>
 inline T *ws_ptr(const cmn_plan *p, size_t byte_off) {
-    return reinterpret_cast<T *>(p->dev_ws + byte_off);
+    return ws_ptr<T>(p->dev_ws, byte_off);
 }
 
 }  // namespace cmn

@@ -122,9 +122,10 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
     if (tpc * plan->C > 0x7fffffffLL) return CMN_ESIZE;
     const dim3 grid(unsigned(tpc * plan->C));
     hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err = hipSuccess;
 #define CMN_LAUNCH_REDUCE(DT)                                                                              \
-    hipLaunchKernelGGL((k_ring_reduce<DT, 16>), grid, dim3(kBlock), 0, s, packed, reduced, scales, (long long)plan->L, \
-                       (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate)
+    err = launch_kernel(k_ring_reduce<DT, 16>, grid, dim3(kBlock), 0, s, packed, reduced, scales, (long long)plan->L, \
+                        (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate)
     const float *const *scales = nullptr;
     if (plan->dtype == CMN_I8S) {
         if (!plan->bound || !plan->have_scales) return CMN_EUNBOUND;
@@ -139,11 +140,11 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
         const long long slots = resident * (kStashFloats / vec_elems(plan->dtype));
         const long long n_launch = (n_tiles + slots - 1) / slots, per_launch = (n_tiles + n_launch - 1) / n_launch;
 #define CMN_LAUNCH_REDUCE2(DT)                                                                                  \
-    for (long long b0 = 0; b0 < n_tiles; b0 += per_launch) {                                                    \
+    for (long long b0 = 0; b0 < n_tiles && err == hipSuccess; b0 += per_launch) {                               \
         const long long e0 = b0 + per_launch < n_tiles ? b0 + per_launch : n_tiles, cnt = e0 - b0;              \
-        hipLaunchKernelGGL((k_ring_reduce_two_phase<DT, 8>), dim3(unsigned(cnt < resident ? cnt : resident)),   \
-                           dim3(kBlock), 0, s, packed, reduced, scales, (long long)plan->L,                     \
-                           (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate, int(b0), int(e0)); \
+        err = launch_kernel(k_ring_reduce_two_phase<DT, 8>, dim3(unsigned(cnt < resident ? cnt : resident)),    \
+                            dim3(kBlock), 0, s, packed, reduced, scales, (long long)plan->L,                    \
+                            (long long)plan->chunk_elems, int(tpc), plan->K, plan->ring_rotate, int(b0), int(e0)); \
     }
         if (plan->dtype == CMN_F32) CMN_LAUNCH_REDUCE2(CMN_F32)
         else if (plan->dtype == CMN_F16) CMN_LAUNCH_REDUCE2(CMN_F16)
@@ -154,5 +155,5 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
     else if (plan->dtype == CMN_BF16) CMN_LAUNCH_REDUCE(CMN_BF16);
     else CMN_LAUNCH_REDUCE(CMN_I8S);
 #undef CMN_LAUNCH_REDUCE
-    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+    return err == hipSuccess ? CMN_OK : CMN_EHIP;
 }

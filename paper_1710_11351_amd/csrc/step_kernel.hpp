@@ -285,39 +285,41 @@ inline int stream_state(const cmn_plan *p) {
 }
 
 template <int DT, int SRC, int MEAN, int OPT>
-inline void launch_k_step(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o, hipStream_t s) {
+inline hipError_t launch_k_step(const cmn_plan *p, const char *ws, int64_t tile_begin, int64_t tile_count,
+                                const OptArgs &o, hipStream_t s) {
     constexpr int U = 16;
-    hipLaunchKernelGGL((k_step<DT, U, SRC, MEAN, OPT>), dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
-                       ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
-                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
+    return launch_kernel(k_step<DT, U, SRC, MEAN, OPT>, dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
+                       ws_ptr<const DeviceTile>(ws, p->ws.tiles) + tile_begin,
+                       ws_ptr<const void *const>(ws, p->ws.grad_cols), ws_ptr<const float *const>(ws, p->ws.scale_ptrs),
                        p->K, 1.0f / float(p->K), o, stream_state<SRC, OPT>(p));
 }
 
 template <int DT, int MEAN, int OPT>
-inline void launch_k_two_phase(const cmn_plan *p, int64_t tile_begin, int64_t tile_count, const OptArgs &o,
-                               hipStream_t s) {
+inline hipError_t launch_k_two_phase(const cmn_plan *p, const char *ws, int64_t tile_begin, int64_t tile_count,
+                                     const OptArgs &o, hipStream_t s) {
     constexpr int U = 8;
     const int64_t resident = two_phase_grid(p);
     const unsigned grid = unsigned(tile_count < resident ? tile_count : resident);
-    hipLaunchKernelGGL((k_step_two_phase<DT, U, MEAN, OPT>), dim3(grid), dim3(kBlock), 0, s,
-                       ws_ptr<const DeviceTile>(p, p->ws.tiles) + tile_begin,
-                       ws_ptr<const void *const>(p, p->ws.grad_cols), ws_ptr<const float *const>(p, p->ws.scale_ptrs),
+    return launch_kernel(k_step_two_phase<DT, U, MEAN, OPT>, dim3(grid), dim3(kBlock), 0, s,
+                       ws_ptr<const DeviceTile>(ws, p->ws.tiles) + tile_begin,
+                       ws_ptr<const void *const>(ws, p->ws.grad_cols), ws_ptr<const float *const>(ws, p->ws.scale_ptrs),
                        p->K, 1.0f / float(p->K), o, int(tile_count), stream_state<SRC_FOLD, OPT>(p));
 }
 
-// Fused step (SRC_FOLD) over tensors [t0, t1): validation shared by the SGD and Adam entry points.
+// Fused step (SRC_FOLD) over tensors [t0, t1) with the tables at device address ws (the workspace a
+// plan was bound to, or any other image of the same layout); `have` says which tensor lists those
+// tables hold.  Validation shared by the SGD and Adam entry points.
 template <int OPT>
-inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, const OptArgs &o, void *stream) {
-    if (int rc = check_launch(plan)) return rc;
+inline int launch_fused_at(const cmn_plan *plan, const char *ws, const BoundLists &have, int t0, int t1, int mean_dest,
+                           const OptArgs &o, void *stream) {
     if (t0 < 0 || t1 < t0 || t1 > plan->T) return CMN_EINVAL;
     if (mean_dest != CMN_MEAN_NONE && mean_dest != CMN_MEAN_TO_MEAN_GRADS && mean_dest != CMN_MEAN_TO_ALL_REPLICAS)
         return CMN_EINVAL;
-    if (!plan->have_grads || !plan->have_opt || (mean_dest == CMN_MEAN_TO_MEAN_GRADS && !plan->have_mean))
-        return CMN_EUNBOUND;
-    if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
+    if (!have.grads || !have.opt || (mean_dest == CMN_MEAN_TO_MEAN_GRADS && !have.mean)) return CMN_EUNBOUND;
+    if (OPT == OPT_ADAM && !have.state2) return CMN_EUNBOUND;
     if (plan->dtype == CMN_I8S) {
         if (mean_dest == CMN_MEAN_TO_ALL_REPLICAS) return CMN_EINVAL;
-        if (!plan->have_scales) return CMN_EUNBOUND;
+        if (!have.scales) return CMN_EUNBOUND;
     }
     const int64_t b = plan->first_tile[size_t(t0)], n = plan->first_tile[size_t(t1)] - b;
     if (n == 0) return CMN_OK;
@@ -327,24 +329,24 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     // workgroups start and drain together) and repays that only over a few thousand tiles: small
     // layer groups of a bucketed step take the one-pass kernel (ResNet-50, K = 32, 16 groups:
     // 739 -> 651 us per step).
-    const bool two_phase = prefer_two_phase_step(plan, OPT == OPT_ADAM ? 12 : 8, mean_dest) &&
-                           (n >= kMinTwoPhaseTiles || plan->step_mode == STEP_TWO_PHASE);
+    const bool two_phase = fused_range_kernel_kind(plan, OPT == OPT_ADAM, mean_dest, n) == 2;
     // One launch of the two-phase kernel covers at most one round of the persistent grid: a
     // kernel boundary realigns the workgroups' phases, which rounds drifting inside one launch
     // would lose (VGG-16, 5.3 rounds: 1931 us in one launch, 1830 us in six).  The tiles are
     // spread evenly over the launches.
     const int64_t slots = two_phase_grid(plan) * (kStashFloats / vec_elems(plan->dtype));
     const int64_t n_launch = (n + slots - 1) / slots, per_launch = (n + n_launch - 1) / n_launch;
+    hipError_t err = hipSuccess;      // of this call's launches only: the runtime's sticky last error is not consulted
 #define CMN_STEP_CASE(DT, MEAN)                                                                          \
     do {                                                                                                 \
         if constexpr (DT != CMN_I8S) {      /* int8 storage never takes the two-phase kernel */          \
             if (two_phase) {                                                                             \
-                for (int64_t b0 = 0; b0 < n; b0 += per_launch)                                           \
-                    launch_k_two_phase<DT, MEAN, OPT>(plan, b + b0, n - b0 < per_launch ? n - b0 : per_launch, o, s); \
+                for (int64_t b0 = 0; b0 < n && err == hipSuccess; b0 += per_launch)                      \
+                    err = launch_k_two_phase<DT, MEAN, OPT>(plan, ws, b + b0, n - b0 < per_launch ? n - b0 : per_launch, o, s); \
                 break;                                                                                   \
             }                                                                                            \
         }                                                                                                \
-        launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, b, n, o, s);                                        \
+        err = launch_k_step<DT, SRC_FOLD, MEAN, OPT>(plan, ws, b, n, o, s);                              \
     } while (0)
 #define CMN_STEP_DTYPE(DT)                                                                  \
     do {                                                                                    \
@@ -359,7 +361,14 @@ inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, con
     else CMN_STEP_CASE(CMN_I8S, CMN_MEAN_TO_MEAN_GRADS);
 #undef CMN_STEP_DTYPE
 #undef CMN_STEP_CASE
-    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+    return err == hipSuccess ? CMN_OK : CMN_EHIP;
+}
+
+// The same on the workspace the plan is bound to.
+template <int OPT>
+inline int launch_fused(const cmn_plan *plan, int t0, int t1, int mean_dest, const OptArgs &o, void *stream) {
+    if (int rc = check_launch(plan)) return rc;
+    return launch_fused_at<OPT>(plan, plan->dev_ws, bound_lists(plan), t0, t1, mean_dest, o, stream);
 }
 
 // Optimizer alone (SRC_MEAN) over all tensors.
@@ -370,8 +379,9 @@ inline int launch_optimizer(const cmn_plan *plan, const OptArgs &o, void *stream
     if (OPT == OPT_ADAM && !plan->have_state2) return CMN_EUNBOUND;
     if (plan->n_tiles == 0) return CMN_OK;
     if (plan->n_tiles > 0x7fffffffLL) return CMN_ESIZE;
-    launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT>(plan, 0, plan->n_tiles, o, static_cast<hipStream_t>(stream));
-    return hipGetLastError() == hipSuccess ? CMN_OK : CMN_EHIP;
+    const hipError_t err = launch_k_step<CMN_F32, SRC_MEAN, CMN_MEAN_NONE, OPT>(plan, plan->dev_ws, 0, plan->n_tiles, o,
+                                                                                static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? CMN_OK : CMN_EHIP;
 }
 
 // lr_t of Adam: the bias corrections of both moments folded into the step size.

@@ -37,10 +37,10 @@ def test_ragged_unaligned_lists_with_ten_replicas(dtype, misalign):
     run_parity(c, steps=2, misalign=misalign)
 
 
-@pytest.mark.parametrize("env", [{"CMN_STEP_KERNEL": "stream"}, {"CMN_TILE_ITERS": "2"}, {"CMN_TILE_ITERS": "5"}])
+@pytest.mark.parametrize("env", [{"CMN_STEP_KERNEL": "stream"}, {"CMN_STEP_KERNEL": "two_phase", "CMN_TWO_PHASE_GRID": "2"}])
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 def test_launch_shape_knobs_do_not_change_results(monkeypatch, env, dtype):
-    """The two environment knobs read at plan creation pick another kernel or tile size; the result
+    """The two environment knobs read at plan creation pick another kernel or grid size; the result
     stays the oracle's, bit for bit (also under a forced kernel kind)."""
     for k, v in env.items():
         monkeypatch.setenv(k, v)

@@ -68,9 +68,11 @@ def test_kernel_entry_points_refuse_an_unbound_plan():
     assert B.cmn_scale_unpack(p.h, 256, 0) == B.CMN_EUNBOUND
     assert B.cmn_momentum_sgd(p.h, .1, .9, 0., 0) == B.CMN_EUNBOUND
     assert B.cmn_allreduce_step(p.h, .1, .9, 0., False, 0) == B.CMN_EUNBOUND
-    # argument checks of the one entry point that needs no binding
+    # argument checks of the one staged entry point that needs no binding (it works on its two buffers alone) ...
     assert B.cmn_ring_reduce(p.h, None, 512, 0) == B.CMN_ENULL
     assert B.cmn_ring_reduce(p.h, 260, 512, 0) == B.CMN_EALIGN
+    # ... except for int8 storage, whose scales come with a binding
+    assert B.cmn_ring_reduce(B.Plan([100, 28], 2, 2, 256, "i8s").h, 256, 512, 0) == B.CMN_EUNBOUND
     assert B.cmn_plan_bind(p.h, None, None, None, None, None, 0) == B.CMN_ENULL
     assert B.cmn_plan_bind(p.h, 260, None, None, None, None, 0) == B.CMN_EALIGN
     assert B.cmn_plan_bind(p.h, 256, None, [1024, 2048], None, None, 0) == B.CMN_ENULL   # p without v
@@ -206,8 +208,16 @@ def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     assert [to_all(K) for K in (7, 8)] == [1, 2]                       # heavy stores: like state beyond the cache
     assert kind(small, 128, "i8s") == 1
     assert B.cmn_plan_step_kernel_kind(None) == -1
+    # a launch over few tiles takes the one-pass kernel whatever the plan-wide rule says, and the
+    # query reports it: whole small lists, and small layer groups of a large list
+    assert B.Plan([4095 * 1024], 32, 1).step_kernel_kind == 1 and B.Plan([4096 * 1024], 32, 1).step_kernel_kind == 2
+    p = B.Plan(small, 32, 32)
+    assert B.cmn_plan_range_kernel_kind(p.h, 0, len(small), 0, 0) == 2
+    assert B.cmn_plan_range_kernel_kind(p.h, 0, 10, 0, 0) == 1           # the stem and first bottleneck: 75 k elements
+    assert B.cmn_plan_range_kernel_kind(p.h, 5, 5, 0, 0) == 1
+    assert B.cmn_plan_range_kernel_kind(p.h, 3, 2, 0, 0) == -1 and B.cmn_plan_range_kernel_kind(p.h, 0, 162, 0, 0) == -1
     monkeypatch.setenv("CMN_STEP_KERNEL", "two_phase")
-    assert kind(small, 2) == 2 and kind(small, 128, "i8s") == 1
+    assert kind(small, 2) == 2 and kind(small, 128, "i8s") == 1 and kind([100], 2) == 2
     monkeypatch.setenv("CMN_STEP_KERNEL", "stream")
     assert kind(small, 32) == 1 and kind(big, 16) == 1
 
@@ -238,21 +248,13 @@ from hypothesis import given, settings, strategies as st
 @settings(max_examples=120, deadline=None)
 @given(numel=st.lists(st.sampled_from([0, 1, 3, 7, 64, 100, 1023, 1024, 1025, 4097, 20000]), min_size=1, max_size=9),
        K=st.integers(1, 9), C=st.integers(1, 7), dtype=st.sampled_from(["f32", "f16", "bf16", "i8s"]),
-       rot=st.integers(0, 1), mis=st.lists(st.integers(0, 7), min_size=4, max_size=4), iters=st.sampled_from([1, 1, 2, 5]))
-def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis, iters):
+       rot=st.integers(0, 1), mis=st.lists(st.integers(0, 7), min_size=4, max_size=4))
+def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis):
     """Coverage, chunk confinement, fold start and vector alignment of every tile, for arbitrary
-    lists, replica counts, chunk counts, storage types, base misalignments and tile sizes."""
+    lists, replica counts, chunk counts, storage types and base misalignments."""
     eb = {"f32": 4, "f16": 2, "bf16": 2, "i8s": 1}[dtype]
     vec = 16 // eb
-    old = os.environ.get("CMN_TILE_ITERS")
-    os.environ["CMN_TILE_ITERS"] = str(iters)         # read by cmn_plan_create
-    try:
-        p = B.Plan(numel, K, C, 256, dtype, rot)
-    finally:
-        if old is None:
-            del os.environ["CMN_TILE_ITERS"]
-        else:
-            os.environ["CMN_TILE_ITERS"] = old
+    p = B.Plan(numel, K, C, 256, dtype, rot)
     base = 1 << 24
     grads = []
     for k in range(K):
@@ -274,7 +276,7 @@ def test_tile_table_invariants_hold_for_any_list(numel, K, C, dtype, rot, mis, i
                B.CMN_HEAD_ADAM_OPT: lambda t: [(mp[t], 4), (pp[t], 4), (vp[t], 4), (sp[t], 4)]}
     for tl in tiles:
         t, e0, ln, c = int(tl["tensor"]), int(tl["e0"]), int(tl["len"]), int(tl["chunk"])
-        assert 0 < ln <= 256 * vec * iters and covered[t] == e0
+        assert 0 < ln <= 256 * vec and covered[t] == e0
         covered[t] += ln
         assert (off[t] + e0) // p.chunk_elems == c == (off[t] + e0 + ln - 1) // p.chunk_elems and c < C
         assert int(tl["start_rank"]) == (c % K if rot else 0)
