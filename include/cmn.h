@@ -239,6 +239,28 @@ int cmn_allreduce_adam_step_range(const cmn_plan *plan, int tensor_begin, int te
 int cmn_adam(const cmn_plan *plan, float alpha, float beta1, float beta2, float eps, float wd, int t,
              void *stream);
 
+/* For callers that cannot allocate device memory or bind a workspace (code under HIP graph
+ * capture, serving loops, harnesses that forbid allocation): cmn_allreduce_step on a plan that
+ * only has to be created, with the tensor lists passed in the call (host arrays as in
+ * cmn_plan_bind; mean_grad_ptrs may be NULL unless mean_dest is CMN_MEAN_TO_MEAN_GRADS).  The
+ * tables cmn_plan_bind would upload go into one CMN_NOALLOC_SCRATCH_BYTES array inside the
+ * library's code object instead (every GPU the library runs on holds its copy until the process
+ * ends), written by small kernels on `stream`; while successive calls on a device pass the same
+ * plan and pointers only the step kernels are launched.  Results are cmn_allreduce_step's, bit
+ * for bit.  The call allocates no device memory, copies nothing from host buffers and does not
+ * wait for the stream.  The current device must be the stream's.  All calls on one GPU share
+ * the one array: calls whose work may overlap there (different streams, or replays of a
+ * captured call next to other calls) race; work queued on one stream is safe.
+ * Errors: CMN_ESIZE if cmn_plan_workspace_bytes(plan) exceeds CMN_NOALLOC_SCRATCH_BYTES (161
+ * tensors x 32 replicas need 1.7 MB, VGG-16 x 16 replicas 8.7 MB), CMN_EINVAL for a CMN_I8S
+ * plan (its scales are bound through a workspace) or an unknown mean_dest, CMN_ENULL,
+ * CMN_EALIGN, CMN_EUNBOUND, CMN_EHIP, CMN_ENOMEM (host). */
+#define CMN_NOALLOC_SCRATCH_BYTES (16 * 1024 * 1024)
+int cmn_allreduce_step_noalloc(cmn_plan *plan, const void *const *grad_ptrs /* host [K*T] */,
+                               void *const *param_ptrs /* host [T] */, void *const *vel_ptrs /* host [T] */,
+                               void *const *mean_grad_ptrs /* host [T] or NULL */, float lr, float mu, float wd,
+                               int mean_dest, void *stream);
+
 /* Static, never NULL. */
 const char *cmn_strerror(int status);
 

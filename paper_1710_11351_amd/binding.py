@@ -98,6 +98,8 @@ def lib() -> ctypes.CDLL:
                                                 ctypes.c_int, vp]
     L.cmn_adam.restype = ctypes.c_int
     L.cmn_adam.argtypes = [vp, f, f, f, f, f, ctypes.c_int, vp]
+    L.cmn_allreduce_step_noalloc.restype = ctypes.c_int
+    L.cmn_allreduce_step_noalloc.argtypes = [vp, vpp, vpp, vpp, vpp, f, f, f, ctypes.c_int, vp]
     L.cmn_strerror.restype = ctypes.c_char_p
     L.cmn_strerror.argtypes = [ctypes.c_int]
     _lib = L
@@ -229,6 +231,15 @@ def cmn_allreduce_step_range(h, tensor_begin: int, tensor_end: int, lr: float, m
                                           _stream(stream))
 
 
+CMN_NOALLOC_SCRATCH_BYTES = 16 * 1024 * 1024
+
+
+def cmn_allreduce_step_noalloc(h, grad_ptrs, param_ptrs, vel_ptrs, mean_grad_ptrs, lr: float, mu: float, wd: float,
+                               mean_dest: int = CMN_MEAN_NONE, stream=None) -> int:
+    return lib().cmn_allreduce_step_noalloc(h, _ptr_array(grad_ptrs), _ptr_array(param_ptrs), _ptr_array(vel_ptrs),
+                                            _ptr_array(mean_grad_ptrs), lr, mu, wd, int(mean_dest), _stream(stream))
+
+
 def cmn_allreduce_adam_step(h, alpha, beta1, beta2, eps, wd, t: int, mean_dest: int = CMN_MEAN_NONE,
                             stream=None) -> int:
     return lib().cmn_allreduce_adam_step(h, alpha, beta1, beta2, eps, wd, int(t), int(mean_dest), _stream(stream))
@@ -309,6 +320,13 @@ class Plan:
     def allreduce_step_range(self, tensor_begin, tensor_end, lr, mu, wd, mean_dest=CMN_MEAN_NONE, stream=None) -> None:
         _check(cmn_allreduce_step_range(self.h, tensor_begin, tensor_end, lr, mu, wd, mean_dest, stream),
                "cmn_allreduce_step_range")
+
+    def allreduce_step_noalloc(self, grads, params, vels, mean_grads, lr, mu, wd, mean_dest=CMN_MEAN_NONE,
+                               stream=None) -> None:
+        """The fused step on an unbound plan with the library's own table array (see cmn.h)."""
+        flat = [g for row in grads for g in row]
+        _check(cmn_allreduce_step_noalloc(self.h, flat, params, vels, mean_grads, lr, mu, wd, mean_dest, stream),
+               "cmn_allreduce_step_noalloc")
 
     def bind_scales(self, scales, stream=None) -> None:
         """scales[k]: CUDA float32 tensor of n_chunks scales of replica k (int8 gradient storage)."""

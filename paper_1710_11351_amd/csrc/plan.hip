@@ -3,6 +3,7 @@
 // tensors.  The geometry follows the contract stated at the top of cmn.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -248,6 +249,8 @@ int cmn_plan_create(cmn_plan **out, int n_tensors, const int64_t *numel, int K, 
 
     cmn_plan *p = new (std::nothrow) cmn_plan;
     if (!p) return CMN_ENOMEM;
+    static std::atomic<uint64_t> next_serial{1};
+    p->serial = next_serial.fetch_add(1);
     try {
         p->T = n_tensors; p->K = K; p->C = n_chunks; p->align_bytes = align_bytes;
         p->dtype = grad_dtype; p->ring_rotate = ring_rotate;

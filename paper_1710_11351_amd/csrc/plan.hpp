@@ -80,6 +80,12 @@ struct cmn_plan {
     char *dev_ws = nullptr;
     std::vector<unsigned char> staging;  // host image of the workspace
 
+    // state of cmn_allreduce_step_noalloc: the pointer arrays of its last call on this plan, the table
+    // image built from them, and a number that changes whenever the image does
+    uint64_t serial = 0;                 // unique per plan created in this process (never reused)
+    uint64_t image_generation = 0;
+    std::vector<const void *> static_inputs;
+    std::vector<unsigned char> static_image;
 };
 
 namespace cmn {

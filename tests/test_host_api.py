@@ -222,6 +222,33 @@ def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     assert kind(small, 32) == 1 and kind(big, 16) == 1
 
 
+def test_noalloc_step_checks_its_arguments_before_touching_the_gpu():
+    """The entry point for callers that cannot allocate keeps its tables in a 16 MiB array inside the
+    library: plans whose tables are larger are refused, and so are int8 plans and missing lists."""
+    numel = [1000, 24]
+    p = B.Plan(numel, 2, 2)
+    g, pp, vp = [1024, 8192, 16384, 32768], [65536, 131072], [262144, 524288]
+    assert B.cmn_allreduce_step_noalloc(None, g, pp, vp, None, .1, .9, 0., 0, 0) == B.CMN_ENULL
+    assert B.cmn_allreduce_step_noalloc(p.h, None, pp, vp, None, .1, .9, 0., 0, 0) == B.CMN_ENULL
+    assert B.cmn_allreduce_step_noalloc(p.h, g, None, vp, None, .1, .9, 0., 0, 0) == B.CMN_ENULL
+    assert B.cmn_allreduce_step_noalloc(p.h, g, pp, [262144, 0], None, .1, .9, 0., 0, 0) == B.CMN_ENULL
+    assert B.cmn_allreduce_step_noalloc(p.h, g, [65538, 131072], vp, None, .1, .9, 0., 0, 0) == B.CMN_EALIGN
+    assert B.cmn_allreduce_step_noalloc(p.h, g, pp, vp, None, .1, .9, 0., 3, 0) == B.CMN_EINVAL
+    assert B.cmn_allreduce_step_noalloc(p.h, g, pp, vp, None, .1, .9, 0., B.CMN_MEAN_TO_MEAN_GRADS, 0) == B.CMN_EUNBOUND
+    p8 = B.Plan(numel, 2, 2, 256, "i8s")
+    assert B.cmn_allreduce_step_noalloc(p8.h, g, pp, vp, None, .1, .9, 0., 0, 0) == B.CMN_EINVAL
+    # one tile record of 64 bytes per 1024 fp32 elements: 300 M elements need more than 16 MiB of tables
+    big = B.Plan([300_000_000], 2, 2)
+    assert big.workspace_bytes > B.CMN_NOALLOC_SCRATCH_BYTES
+    assert B.cmn_allreduce_step_noalloc(big.h, [1024, 2048], [4096], [8192], None, .1, .9, 0., 0, 0) == B.CMN_ESIZE
+    from paper_1710_11351_amd import workloads as wl
+    for cfg in (3, 4, 5):                            # the benchmark workloads all fit
+        c = wl.config(cfg)
+        assert B.Plan(c.numel, c.K, c.n_chunks, 256, c.grad_dtype).workspace_bytes <= B.CMN_NOALLOC_SCRATCH_BYTES
+    empty = B.Plan([0, 0], 2, 2)                     # nothing to do: no GPU call is made
+    assert B.cmn_allreduce_step_noalloc(empty.h, [0, 0, 0, 0], [0, 0], [0, 0], None, .1, .9, 0., 0, 0) == B.CMN_OK
+
+
 def test_empty_plans():
     for numel in ([], [0, 0]):
         p = B.Plan(numel, 4, 4)
