@@ -130,6 +130,9 @@ size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_
  * is not inside the list. */
 int cmn_plan_step_kernel_kind(const cmn_plan *plan, int adam, int mean_dest);
 int cmn_plan_range_kernel_kind(const cmn_plan *plan, int tensor_begin, int tensor_end, int adam, int mean_dest);
+/* Number of kernel launches that fused step makes (kind 2 takes one launch per round of its
+ * persistent grid; 0 for an empty range, -1 as above). */
+int cmn_plan_range_launch_count(const cmn_plan *plan, int tensor_begin, int tensor_end, int adam, int mean_dest);
 
 /* Pure host: compute the work-unit table that cmn_plan_bind would upload for these
  * pointer arrays (same meaning as in cmn_plan_bind; addresses are only inspected,

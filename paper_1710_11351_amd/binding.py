@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
     L.cmn_plan_step_kernel_kind.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     L.cmn_plan_range_kernel_kind.restype = ctypes.c_int
     L.cmn_plan_range_kernel_kind.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    L.cmn_plan_range_launch_count.restype = ctypes.c_int
+    L.cmn_plan_range_launch_count.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     L.cmn_plan_workspace_bytes.restype = ctypes.c_size_t
     L.cmn_plan_workspace_bytes.argtypes = [vp]
     L.cmn_plan_describe_tiles.restype = ctypes.c_int
@@ -176,6 +178,10 @@ def cmn_plan_step_kernel_kind(h, adam: int = 0, mean_dest: int = 0) -> int:
 
 def cmn_plan_range_kernel_kind(h, tensor_begin: int, tensor_end: int, adam: int = 0, mean_dest: int = 0) -> int:
     return lib().cmn_plan_range_kernel_kind(h, int(tensor_begin), int(tensor_end), int(adam), int(mean_dest))
+
+
+def cmn_plan_range_launch_count(h, tensor_begin: int, tensor_end: int, adam: int = 0, mean_dest: int = 0) -> int:
+    return lib().cmn_plan_range_launch_count(h, int(tensor_begin), int(tensor_end), int(adam), int(mean_dest))
 
 
 def cmn_plan_workspace_bytes(h) -> int:

@@ -4,6 +4,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <utility>
 #include <vector>
 
 #include "../../include/cmn.h"
@@ -105,6 +106,7 @@ bool prefer_two_phase_reduce(const cmn_plan *p);
 bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem /* 8: p + velocity, 12: p + both Adam moments */,
                            int mean_dest);
 int64_t two_phase_grid(const cmn_plan *p);
+std::pair<int64_t, int64_t> two_phase_launches(const cmn_plan *p, int64_t n_tiles);   // (launches, tiles per launch)
 
 // 1 (one pass) or 2 (two-phase) for a fused-step launch over n_tiles tiles of this plan.
 int fused_range_kernel_kind(const cmn_plan *p, bool adam, int mean_dest, int64_t n_tiles);

@@ -137,8 +137,7 @@ extern "C" int cmn_ring_reduce(const cmn_plan *plan, const void *packed, float *
         // one launch per round of the persistent grid, tiles spread evenly (a kernel boundary
         // realigns the phases of the workgroups)
         const long long n_tiles = tpc * plan->C, resident = two_phase_grid(plan);
-        const long long slots = resident * (kStashFloats / vec_elems(plan->dtype));
-        const long long n_launch = (n_tiles + slots - 1) / slots, per_launch = (n_tiles + n_launch - 1) / n_launch;
+        const long long per_launch = two_phase_launches(plan, n_tiles).second;
 #define CMN_LAUNCH_REDUCE2(DT)                                                                                  \
     for (long long b0 = 0; b0 < n_tiles && err == hipSuccess; b0 += per_launch) {                               \
         const long long e0 = b0 + per_launch < n_tiles ? b0 + per_launch : n_tiles, cnt = e0 - b0;              \

@@ -330,12 +330,7 @@ inline int launch_fused_at(const cmn_plan *plan, const char *ws, const BoundList
     // layer groups of a bucketed step take the one-pass kernel (ResNet-50, K = 32, 16 groups:
     // 739 -> 651 us per step).
     const bool two_phase = fused_range_kernel_kind(plan, OPT == OPT_ADAM, mean_dest, n) == 2;
-    // One launch of the two-phase kernel covers at most one round of the persistent grid: a
-    // kernel boundary realigns the workgroups' phases, which rounds drifting inside one launch
-    // would lose (VGG-16, 5.3 rounds: 1931 us in one launch, 1830 us in six).  The tiles are
-    // spread evenly over the launches.
-    const int64_t slots = two_phase_grid(plan) * (kStashFloats / vec_elems(plan->dtype));
-    const int64_t n_launch = (n + slots - 1) / slots, per_launch = (n + n_launch - 1) / n_launch;
+    const int64_t per_launch = two_phase_launches(plan, n).second;   // one launch per round of the persistent grid
     hipError_t err = hipSuccess;      // of this call's launches only: the runtime's sticky last error is not consulted
 #define CMN_STEP_CASE(DT, MEAN)                                                                          \
     do {                                                                                                 \

@@ -338,10 +338,15 @@ def test_config5_vgg16_k16_adam_staged_full_size():
 
 def test_more_than_2_to_31_elements_full_size(monkeypatch):
     """One tensor of 2^31 + 5000 binary16 elements (offsets beyond 32 bits in every kernel), two replicas.
-    The oracle cannot hold this, so the check is against the same arithmetic written with torch's
-    elementwise fp32 operations, each of which rounds once: (g0 + g1) * 0.5, mu*v - lr*g, p + v."""
+    The oracle cannot hold this whole, so every element is checked against the same arithmetic written with
+    torch's elementwise fp32 operations, each of which rounds once: (g0 + g1) * 0.5, mu*v - lr*g, p + v; and the
+    oracle itself is run on windows of the big tensor (its start, the elements around packed index 2^31, around
+    the ring-chunk edge, its tail) and on the two small tensors.  With two replicas the fold is one addition,
+    which commutes, so a window's result does not depend on where the window lies."""
     import torch
+    import oracle
     from paper_1710_11351_amd import binding as B
+    from parity_util import assert_bit_equal
     n = (1 << 31) + 5000
     numel = [777, n, 3]
     gen = torch.Generator(device="cuda").manual_seed(4242)
@@ -362,12 +367,31 @@ def test_more_than_2_to_31_elements_full_size(monkeypatch):
         nv = mu * v[t] - lr * mean
         want_m.append(mean); want_v.append(nv); want_p.append(p[t] + nv)
     plan = B.Plan(numel, 2, 2, 256, "f16")
+    edge, at31 = plan.chunk_elems - numel[0], (1 << 31) - numel[0]       # tensor coordinates of the chunk edge / packed 2^31
+    windows = [(0, 0, numel[0]), (2, 0, numel[2]), (1, 0, 4096), (1, at31 - 2048, at31 + 2048),
+               (1, edge - 2048, edge + 2048), (1, n - 4096, n)]
+    p_host = {w: p[w[0]][w[1]:w[2]].cpu().numpy() for w in windows}       # state before any step
+    v_host = {w: v[w[0]][w[1]:w[2]].cpu().numpy() for w in windows}
+
+    def oracle_windows(what, got_m, got_p=None, got_v=None):
+        for w in windows:
+            t, lo, hi = w
+            geo = oracle.Geometry([hi - lo], 1, 256, "f16")
+            packed_o = [oracle.pack(geo, [g[k][t][lo:hi].cpu().numpy()]) for k in range(2)]
+            mean_o = oracle.unpack(geo, oracle.scale(oracle.direct_fold(geo, packed_o, 1), 2))[0]
+            assert_bit_equal(got_m[t][lo:hi].cpu().numpy(), mean_o, f"{what} mean, window {w}")
+            if got_p is not None:
+                p_o, v_o = p_host[w].copy(), v_host[w].copy()
+                oracle.momentum_sgd(mean_o, p_o, v_o, lr, mu, 0.0)
+                assert_bit_equal(got_p[t][lo:hi].cpu().numpy(), p_o, f"{what} p, window {w}")
+                assert_bit_equal(got_v[t][lo:hi].cpu().numpy(), v_o, f"{what} v, window {w}")
     # staged entry points first (they leave p and v untouched until cmn_momentum_sgd, which is skipped)
     plan.bind(g, p, v, m_fused)
     packed = torch.empty(2 * plan.L, dtype=torch.float16, device="cuda")
     reduced = torch.empty(plan.L, dtype=torch.float32, device="cuda")
     plan.pack(packed); plan.ring_reduce(packed, reduced); plan.scale_unpack(reduced)
     torch.cuda.synchronize()
+    oracle_windows("staged", m_fused)
     for t in range(len(numel)):
         assert torch.equal(m_fused[t].view(torch.int32), want_m[t].view(torch.int32)), f"staged mean, tensor {t}"
         m_fused[t].zero_()
@@ -381,6 +405,7 @@ def test_more_than_2_to_31_elements_full_size(monkeypatch):
         plan.bind(g, p, v, m_fused)
         plan.allreduce_step(lr, mu, 0.0, write_mean_grad=True)
         torch.cuda.synchronize()
+        oracle_windows(mode, m_fused, p, v)
         for t in range(len(numel)):
             for name, a, b in (("mean", m_fused, want_m), ("v", v, want_v), ("p", p, want_p)):
                 assert torch.equal(a[t].view(torch.int32), b[t].view(torch.int32)), f"{mode} {name}, tensor {t}"

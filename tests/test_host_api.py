@@ -330,14 +330,46 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0 and "one GPU" in (r.stdout + r.stderr)
 
 
-def test_algorithmic_bytes_match_the_stated_formulas():
-    """bench.py prices a launch at (K*e_g + 16)*N bytes (+4N with the mean stored, +K*e_g*N handed back to all
-    replicas, +8N for Adam's second moment) and the staged entry points at 2*K*e_g*N, (K*e_g+4)*N, 8N, 20N."""
+def _bench_module():
     import importlib.util
-    from paper_1710_11351_amd import workloads as wl
     spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(ROOT, "bench.py"))
     bench = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(bench)
+    return bench
+
+
+def test_bench_quotes_counter_traffic_only_for_the_profiled_workload_and_kernel(tmp_path):
+    """roofline.traffic comes from a committed rocprofv3 counter summary and is null unless the workload and
+    the kernel instance that was launched are the ones that summary measured."""
+    bench = _bench_module()
+    (tmp_path / "some_pmc.txt").write_text(
+        "prose ...\nTRAFFIC workload=resnet50_k32_f32 kernel=k_step_two_phase<0,8,0,0> launches_per_step=1 bytes_per_step=3691800000\n"
+        "TRAFFIC workload=vgg16_k16_f32 kernel=k_step_two_phase<0,8,0,0> launches_per_step=6 bytes_per_step=11100000000\n")
+    (tmp_path / "kernel_stats.txt").write_text("TRAFFIC workload=resnet50_k32_f32 kernel=k_step<0,16,0,0,0> launches_per_step=1 bytes_per_step=1\n")
+    d = str(tmp_path)
+    got, src = bench.profiled_traffic("resnet50_k32_f32", "k_step_two_phase<0,8,0,0>", 1, d)
+    assert got == 3_691_800_000 and src.endswith("some_pmc.txt")
+    assert bench.profiled_traffic("vgg16_k16_f32", "k_step_two_phase<0,8,0,0>", 6, d)[0] == 11_100_000_000
+    assert bench.profiled_traffic("resnet50_k32_f32", "k_step<0,16,0,0,0>", 1, d) == (None, None)      # forced one-pass kernel
+    assert bench.profiled_traffic("resnet50_k32_f32+bf16", "k_step_two_phase<2,8,0,0>", 1, d) == (None, None)   # other storage type
+    assert bench.profiled_traffic("resnet50_k32_f32", "k_step_two_phase<0,8,1,0>", 1, d) == (None, None)  # mean gradient stored
+    assert bench.profiled_traffic("vgg16_k16_f32", "k_step_two_phase<0,8,0,0>", 5, d) == (None, None)     # another launch split
+    assert bench.step_kernel_name("f32", 2, 0, "sgd") == "k_step_two_phase<0,8,0,0>"
+    assert bench.step_kernel_name("i8s", 1, 1, "adam") == "k_step<3,16,0,1,1>"
+    # every summary under profiles/ that carries such lines parses, and names a kernel of this library
+    import glob
+    for path in glob.glob(os.path.join(ROOT, "profiles", "*pmc*.txt")):
+        for line in open(path):
+            if line.startswith("TRAFFIC "):
+                kv = dict(x.split("=", 1) for x in line.split()[1:])
+                assert kv["kernel"].startswith("k_step") and int(kv["bytes_per_step"]) > 0 and int(kv["launches_per_step"]) > 0
+
+
+def test_algorithmic_bytes_match_the_stated_formulas():
+    """bench.py prices a launch at (K*e_g + 16)*N bytes (+4N with the mean stored, +K*e_g*N handed back to all
+    replicas, +8N for Adam's second moment) and the staged entry points at 2*K*e_g*N, (K*e_g+4)*N, 8N, 20N."""
+    from paper_1710_11351_amd import workloads as wl
+    bench = _bench_module()
     c = wl.config(3)
     N, K = c.N, c.K
     assert bench.algorithmic_bytes(c, "step", 0, "sgd") == (4 * K + 16) * N == 3_680_212_608
