@@ -535,3 +535,29 @@ def test_int8_fold_equals_fold_of_decoded_float32():
         a = oracle.direct_fold(geo8, q, rot, scales)
         b = oracle.direct_fold(geo32, dec, rot)
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_fp16_storage_tolerance_reading_on_the_config4_distribution():
+    """north_star's "2e-3 relative" for the fp16-storage path, read two ways on config 4's value distribution
+    (N(0, 1e-3), 1 % of the elements at 100x, 128 replicas): against 2e-3 * max(|b|, rms_t(b)), the form first
+    proposed, one element in 590 k sits 4 % over the bar (an element whose replicas hold an outlier moves by that
+    outlier's rounding error, which the tensor-wide rms knows nothing about); against 2e-3 * max(|b|, mean_k |g_k|),
+    the magnitudes that were actually summed, the worst element uses less than a fifth of the bar.  The oracle's own
+    arithmetic is exact here (decode and fp32 sums), so this is a statement about the inputs' quantisation only."""
+    import dataclasses
+    c4 = wl.config(4)
+    numel = [36864, 64, 64, 147456, 1000, 4096, 589824]
+    c = dataclasses.replace(wl.custom_config(numel, K=128, n_chunks=128, grad_dtype="f16", cfg=97, grad_std=c4.grad_std,
+                                             outlier_frac=c4.outlier_frac), outlier_scale=c4.outlier_scale)
+    g16 = [wl.gen_grads(c, 0, k) for k in range(c.K)]
+    g32 = [wl.gen_grads_f32_unquantised(c, 0, k) for k in range(c.K)]
+    mean = oracle.mean_gradients(g16, numel, c.n_chunks, dtype="f16")
+    worst_rms, worst_mag = 0.0, 0.0
+    for t in range(len(numel)):
+        st = np.stack([g[t].astype(np.float64) for g in g32])
+        want, mag = st.mean(axis=0), np.abs(st).mean(axis=0)
+        err = np.abs(mean[t] - want)
+        worst_rms = max(worst_rms, float((err / (2e-3 * np.maximum(np.abs(want), np.sqrt(np.mean(want ** 2))))).max()))
+        worst_mag = max(worst_mag, float((err / (2e-3 * np.maximum(np.abs(want), mag))).max()))
+    assert 1.0 < worst_rms < 1.1          # the rms form fails, narrowly
+    assert worst_mag < 0.25               # the per-element form holds with more than 4x headroom
