@@ -90,3 +90,45 @@ def test_config3_resnet50_k32_full_size_matches_the_bound_step():
     ref, na, plan = _pair(c)
     _step_both(c, ref, na, plan, 0, B.CMN_MEAN_NONE)
     _step_both(c, ref, na, plan, 1, B.CMN_MEAN_TO_MEAN_GRADS)
+
+
+def test_captured_into_a_hip_graph_and_replayed_between_eager_calls():
+    """Under stream capture the table writes and the step kernels become kernel nodes of the graph; every replay
+    rewrites the array for its own plan, and eager calls of another plan in between rewrite it for theirs (after a
+    capture the host never assumes it knows what the array holds)."""
+    import torch
+    a = wl.custom_config([4096, 64, 36864, 256, 9408, 1000], K=4, n_chunks=4, cfg=68)
+    b = wl.custom_config([1000, 24, 5000], K=3, n_chunks=2, cfg=67)
+    ra, na, pa = _pair(a)
+    rb, nb, pb = _pair(b)
+    for (ref, got), c in (((ra, na), a), ((rb, nb), b)):
+        g = gen_all_grads(c, 0)
+        for dc in (ref, got):
+            for k in range(c.K):
+                dc.set_grads(k, g[k])
+    pb.allreduce_step_noalloc(nb.grads, nb.p, nb.v, None, b.lr, b.mu, b.wd)          # the array holds b's tables
+    rb.plan.allreduce_step(b.lr, b.mu, b.wd)
+    torch.cuda.synchronize()
+    stream, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        graph.capture_begin()
+        pa.allreduce_step_noalloc(na.grads, na.p, na.v, na.m, a.lr, a.mu, a.wd, mean_dest=B.CMN_MEAN_TO_MEAN_GRADS,
+                                  stream=stream)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for step in range(3):
+        g = gen_all_grads(a, step + 1)
+        for dc in (ra, na):
+            for k in range(a.K):
+                dc.set_grads(k, g[k])
+        torch.cuda.synchronize()
+        graph.replay()
+        ra.plan.allreduce_step(a.lr, a.mu, a.wd, mean_dest=B.CMN_MEAN_TO_MEAN_GRADS)
+        torch.cuda.synchronize()
+        pb.allreduce_step_noalloc(nb.grads, nb.p, nb.v, None, b.lr, b.mu, b.wd)      # eager, other plan, same array
+        rb.plan.allreduce_step(b.lr, b.mu, b.wd)
+        torch.cuda.synchronize()
+        for ref, got, name in ((ra, na, "graph"), (rb, nb, "eager")):
+            for t, (x, y) in enumerate(zip(got.get(got.p) + got.get(got.v) + got.get(got.m),
+                                           ref.get(ref.p) + ref.get(ref.v) + ref.get(ref.m))):
+                assert_bit_equal(x, y, f"replay {step} {name} tensor {t}")
