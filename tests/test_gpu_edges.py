@@ -202,3 +202,32 @@ def test_config3_resnet50_k32_every_chunk_folded_from_rank_0_full_size():
     """The other reading of "ring reduction in rank order" (ring_rotate = 0) on the benchmark workload."""
     from parity_util import run_parity
     run_parity(wl.config(3), steps=1, ring_rotate=0)
+
+
+# ---- the widened variants bench.py times and profiles/ records, at the benchmark's full size ----
+@pytest.mark.parametrize("dtype", ["bf16", "i8s"])
+def test_config3_resnet50_k32_compressed_storage_full_size(dtype):
+    """ResNet-50 x 32 replicas with bfloat16 (two-phase kernel) and int8 + per-chunk scales (one-pass kernel)."""
+    import dataclasses
+    from parity_util import run_parity
+    c = dataclasses.replace(wl.config(3), grad_dtype=dtype, name=f"resnet50_k32_{dtype}")
+    run_parity(c, steps=1, check_packed=False)
+
+
+def test_config3_resnet50_k32_average_to_all_replicas_full_size():
+    """The all-gather half on the benchmark workload: all 32 replicas' 161 tensors end up holding the average."""
+    c = wl.config(3)
+    dc = DeviceCase(c, with_mean=False)
+    p_o, v_o = [x.copy() for x in wl.gen_params(c)], wl.gen_velocity(c)
+    dc.set_state(p_o, v_o)
+    grads = gen_all_grads(c, 0)
+    for k in range(c.K):
+        dc.set_grads(k, grads[k])
+    mean_o = oracle.allreduce_step(grads, p_o, v_o, c.n_chunks, c.lr, c.mu, c.wd)
+    del grads
+    dc.plan.allreduce_step(c.lr, c.mu, c.wd, mean_dest=B.CMN_MEAN_TO_ALL_REPLICAS)
+    for k in range(c.K):
+        for t, (a, b) in enumerate(zip(dc.get(dc.grads[k]), mean_o)):
+            assert_bit_equal(a, b, f"replica {k} tensor {t}")
+    for t, (a, b) in enumerate(zip(dc.get(dc.p) + dc.get(dc.v), p_o + v_o)):
+        assert_bit_equal(a, b, f"state {t}")

@@ -216,6 +216,13 @@ def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     assert B.cmn_plan_range_kernel_kind(p.h, 0, 10, 0, 0) == 1           # the stem and first bottleneck: 75 k elements
     assert B.cmn_plan_range_kernel_kind(p.h, 5, 5, 0, 0) == 1
     assert B.cmn_plan_range_kernel_kind(p.h, 3, 2, 0, 0) == -1 and B.cmn_plan_range_kernel_kind(p.h, 0, 162, 0, 0) == -1
+    # launches per fused step: one per round of the persistent grid (512 workgroups x 50 tiles when the device
+    # cannot be asked, as here), one for the one-pass kernel, none for an empty range
+    assert B.cmn_plan_range_launch_count(p.h, 0, len(small), 0, 0) == 1 and B.cmn_plan_range_launch_count(p.h, 0, 10, 0, 0) == 1
+    assert B.cmn_plan_range_launch_count(p.h, 5, 5, 0, 0) == 0 and B.cmn_plan_range_launch_count(p.h, 0, 162, 0, 0) == -1
+    pv = B.Plan(big, 16, 16)
+    assert B.cmn_plan_range_launch_count(pv.h, 0, len(big), 0, 0) == 6 and B.cmn_plan_range_launch_count(pv.h, 0, len(big), 1, 0) == 6
+    assert B.cmn_plan_range_launch_count(B.Plan(small, 128, 128, 256, "f16").h, 0, len(small), 0, 0) == 1
     monkeypatch.setenv("CMN_STEP_KERNEL", "two_phase")
     assert kind(small, 2) == 2 and kind(small, 128, "i8s") == 1 and kind([100], 2) == 2
     monkeypatch.setenv("CMN_STEP_KERNEL", "stream")
