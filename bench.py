@@ -60,9 +60,11 @@ def algorithmic_bytes(c, entry="step", mean_dest=0, opt="sgd"):
 
 def step_kernel_name(grad_dtype, kind, mean_dest, opt):
     """Name of the kernel instance a fused step launches, as rocprofv3 prints it (template arguments:
-    storage type, loads in flight, [gradient source,] mean destination, optimizer)."""
+    storage type, loads in flight, [gradient source,] mean destination, optimizer; kind as reported by
+    cmn_plan_range_kernel_kind)."""
     dt, o = DT_CODE[grad_dtype], int(opt == "adam")
-    return (f"k_step_two_phase<{dt},8,{mean_dest},{o}>" if kind == 2 else f"k_step<{dt},16,0,{mean_dest},{o}>")
+    return {1: f"k_step<{dt},16,0,{mean_dest},{o}>", 2: f"k_step_two_phase<{dt},8,{mean_dest},{o}>",
+            3: f"k_step_state_first<16,{mean_dest},{o}>"}[kind]
 
 
 def profiled_traffic(workload, kernel, launches_per_step, profiles_dir=None):

@@ -126,8 +126,9 @@ size_t cmn_plan_workspace_bytes(const cmn_plan *plan); /* device bytes cmn_plan_
  * (adam != 0) and the given cmn_mean_dest, over the whole list or over tensors
  * [tensor_begin, tensor_end): a tuning decision that never changes results; for benchmarks and
  * profiles.  1 = one pass, a workgroup per tile; 2 = persistent grid that reads first and
- * writes afterwards (small lists and layer groups use kind 1); -1 if plan is NULL or the range
- * is not inside the list. */
+ * writes afterwards (small lists and layer groups use kind 1); 3 = kind 1 with parameters and
+ * state requested ahead of the gradients (at most 4 float32 replicas); -1 if plan is NULL or
+ * the range is not inside the list. */
 int cmn_plan_step_kernel_kind(const cmn_plan *plan, int adam, int mean_dest);
 int cmn_plan_range_kernel_kind(const cmn_plan *plan, int tensor_begin, int tensor_end, int adam, int mean_dest);
 /* Number of kernel launches that fused step makes (kind 2 takes one launch per round of its

@@ -162,6 +162,13 @@ bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem, int mean
     return p->K * elem_bytes(p->dtype) >= (light_stores ? 56 : 32);
 }
 
+// Few fp32 replicas, the average stored at most once, state that stays in the memory-side cache: the one-pass
+// kernel that requests parameters and state ahead of the gradients (see k_step_state_first).
+bool state_first_step(const cmn_plan *p, int state_bytes_per_elem, int mean_dest) {
+    return p->dtype == CMN_F32 && p->K <= kStateFirstReplicas && mean_dest != CMN_MEAN_TO_ALL_REPLICAS &&
+           !beyond_cache(double(p->N) * state_bytes_per_elem);
+}
+
 int check_ptr_array(const cmn_plan *p, const void *const *ptrs, int rows, unsigned elem_bytes) {
     for (int r = 0; r < rows; ++r)
         for (int t = 0; t < p->T; ++t) {
@@ -219,9 +226,9 @@ void fill_table_image(const cmn_plan *p, unsigned char *img, const void *const *
 }
 
 int fused_range_kernel_kind(const cmn_plan *p, bool adam, int mean_dest, int64_t n_tiles) {
-    return prefer_two_phase_step(p, adam ? 12 : 8, mean_dest) &&
-                   (n_tiles >= kMinTwoPhaseTiles || p->step_mode == STEP_TWO_PHASE)
-               ? 2 : 1;
+    if (prefer_two_phase_step(p, adam ? 12 : 8, mean_dest) && (n_tiles >= kMinTwoPhaseTiles || p->step_mode == STEP_TWO_PHASE))
+        return 2;
+    return state_first_step(p, adam ? 12 : 8, mean_dest) ? 3 : 1;
 }
 
 // One launch of a two-phase kernel covers at most one round of the persistent grid (a kernel

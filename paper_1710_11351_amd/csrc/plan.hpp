@@ -24,6 +24,9 @@ constexpr int kStashFloats = 200;
 
 enum { STEP_AUTO = 0, STEP_ONE_PASS = 1, STEP_TWO_PHASE = 2 };
 
+// Up to this many fp32 replicas the one-pass fused step requests parameters and state ahead of the gradients.
+constexpr int kStateFirstReplicas = 4;
+
 // Fewer tiles than this in one launch of the fused step: the one-pass kernel, whatever the plan-wide choice.
 constexpr int64_t kMinTwoPhaseTiles = 4096;
 
@@ -105,10 +108,11 @@ int device_compute_units();
 bool prefer_two_phase_reduce(const cmn_plan *p);
 bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem /* 8: p + velocity, 12: p + both Adam moments */,
                            int mean_dest);
+bool state_first_step(const cmn_plan *p, int state_bytes_per_elem, int mean_dest);
 int64_t two_phase_grid(const cmn_plan *p);
 std::pair<int64_t, int64_t> two_phase_launches(const cmn_plan *p, int64_t n_tiles);   // (launches, tiles per launch)
 
-// 1 (one pass) or 2 (two-phase) for a fused-step launch over n_tiles tiles of this plan.
+// 1 (one pass), 3 (one pass, state first) or 2 (two-phase) for a fused-step launch over n_tiles tiles of this plan.
 int fused_range_kernel_kind(const cmn_plan *p, bool adam, int mean_dest, int64_t n_tiles);
 
 // Which tensor lists a table image holds.

@@ -179,6 +179,38 @@ struct TileView {
         }
     }
 
+    // The one-pass step of a list with few fp32 replicas, where parameter and state fetches are a large share
+    // of a tile's reads: they are requested before the fold, so that they travel together with the gradients,
+    // and everything is stored afterwards (Q = 1: run order and dealt order coincide).
+    template <int U>
+    __device__ __forceinline__ void state_first_step(int vi0, const float *const *scale_ptrs, int K, float inv_k,
+                                                     const OptArgs &o, f32x4 *deal_buf) const {
+        static_assert(Q == 1 && SRC == SRC_FOLD && MEAN != CMN_MEAN_TO_ALL_REPLICAS, "fp32 gradients, average stored at most once");
+        const unsigned x = (unsigned(vi0) + threadIdx.x) * 4u, end = unsigned(nvec) * 4u;
+        f32x4 pv = {}, s1v = {}, s2v = {};
+        if (x < end) {
+            pv = load_vec<f32x4>(p + head + x);
+            s1v = load_vec<f32x4>(s1 + head + x);
+            if (ADAM) s2v = load_vec<f32x4>(s2 + head + x);
+        }
+        f32x4 g[1];
+        averaged<U>(g, vi0 + int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
+        if (x < end) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float pi = pv[i], a = s1v[i], b = ADAM ? s2v[i] : 0.0f;
+                opt_update<OPT>(g[0][i], pi, a, b, o);
+                pv[i] = pi; s1v[i] = a;
+                if (ADAM) s2v[i] = b;
+            }
+            const unsigned bytes = unsigned(len) * 4u, off = (unsigned(head) + x) * 4u;
+            if (MEAN == CMN_MEAN_TO_MEAN_GRADS) store_vec<kStoreAverage>(make_rsrc(m, bytes), off, g[0]);
+            if (ADAM) store_vec<kStoreStateOnePass>(make_rsrc(s2, bytes), off, s2v);
+            store_vec<kStoreStateOnePass>(make_rsrc(s1, bytes), off, s1v);
+            store_vec<kStoreStateOnePass>(make_rsrc(p, bytes), off, pv);
+        }
+    }
+
     // ragged head and tail of the tile (or the whole tile when its streams share no alignment):
     // one element per thread, start to finish
     __device__ __forceinline__ void ragged(const float *const *scale_ptrs, int K, float inv_k, const OptArgs &o) const {
@@ -235,6 +267,20 @@ __global__ __launch_bounds__(kBlock) void k_step(
     tv.ragged(scale_ptrs, K, inv_k, o);
 }
 
+// The same for lists of at most kStateFirstReplicas fp32 replicas whose state stays in the memory-side cache:
+// parameters and state are requested ahead of the gradients (ResNet-50, K = 4: 118 -> 116 us, with Adam
+// 170 -> 165 us).  From about 8 replicas on that only delays the gradient loads (K = 12 cold: 272 -> 276 us), and
+// narrow storage types would pay for holding their 2 or 4 float4s per stream across the fold with occupancy.
+template <int U, int MEAN, int OPT>
+__global__ __launch_bounds__(kBlock) void k_step_state_first(
+    const DeviceTile *__restrict__ tiles, const void *const *__restrict__ grad_cols, int K, float inv_k, OptArgs o) {
+    using TV = TileView<CMN_F32, SRC_FOLD, MEAN, OPT>;
+    __shared__ f32x4 deal_buf[1];
+    const TV tv(load_tile(tiles, blockIdx.x), grad_cols, K);
+    for (int vi0 = 0; vi0 < tv.nvec; vi0 += kBlock) tv.template state_first_step<U>(vi0, nullptr, K, inv_k, o, deal_buf);
+    tv.ragged(nullptr, K, inv_k, o);
+}
+
 // Two-phase persistent kernel for the fused step.  Mixing even a few stores into a saturated
 // read stream slows the reads on MI355X by far more than the stores' byte share, so the
 // work is ordered to keep them apart in time: a workgroup first folds the gradients of up
@@ -288,6 +334,12 @@ template <int DT, int SRC, int MEAN, int OPT>
 inline hipError_t launch_k_step(const cmn_plan *p, const char *ws, int64_t tile_begin, int64_t tile_count,
                                 const OptArgs &o, hipStream_t s) {
     constexpr int U = 16;
+    if constexpr (DT == CMN_F32 && SRC == SRC_FOLD && MEAN != CMN_MEAN_TO_ALL_REPLICAS) {
+        if (state_first_step(p, OPT == OPT_ADAM ? 12 : 8, MEAN))
+            return launch_kernel(k_step_state_first<U, MEAN, OPT>, dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
+                                 ws_ptr<const DeviceTile>(ws, p->ws.tiles) + tile_begin,
+                                 ws_ptr<const void *const>(ws, p->ws.grad_cols), p->K, 1.0f / float(p->K), o);
+    }
     return launch_kernel(k_step<DT, U, SRC, MEAN, OPT>, dim3(unsigned(tile_count)), dim3(kBlock), 0, s,
                        ws_ptr<const DeviceTile>(ws, p->ws.tiles) + tile_begin,
                        ws_ptr<const void *const>(ws, p->ws.grad_cols), ws_ptr<const float *const>(ws, p->ws.scale_ptrs),

@@ -196,17 +196,19 @@ def test_kernel_kind_follows_the_measured_rule(monkeypatch):
     monkeypatch.delenv("CMN_STEP_KERNEL", raising=False)
     small, big = wl.config(3).numel, wl.config(5).numel
     kind = lambda numel, K, dt="f32": B.Plan(numel, K, K, 256, dt).step_kernel_kind
-    assert [kind(small, K) for K in (4, 8, 13, 14, 32)] == [1, 1, 1, 2, 2]
+    assert [kind(small, K) for K in (1, 4, 5, 8, 13, 14, 32)] == [3, 3, 1, 1, 1, 2, 2]    # 3: one pass, state requested first
     assert [kind(small, K, "f16") for K in (16, 27, 28, 128)] == [1, 1, 2, 2]
     assert [kind(big, K) for K in (4, 7, 8, 16)] == [1, 1, 2, 2]
     assert [kind(big, K, "bf16") for K in (8, 15, 16)] == [1, 1, 2]
     adam = lambda numel, K, dt="f32": B.Plan(numel, K, K, 256, dt).adam_step_kernel_kind
-    assert [adam(small, K) for K in (4, 7, 8, 32)] == [1, 1, 2, 2]     # both moments: 306 MB, beyond the cache
+    assert [adam(small, K) for K in (4, 7, 8, 32)] == [3, 1, 2, 2]     # both moments: 306 MB, beyond the cache
     def to_all(K):
         p = B.Plan(small, K, K)
         return B.cmn_plan_step_kernel_kind(p.h, 0, B.CMN_MEAN_TO_ALL_REPLICAS)
     assert [to_all(K) for K in (7, 8)] == [1, 2]                       # heavy stores: like state beyond the cache
-    assert kind(small, 128, "i8s") == 1
+    assert kind(small, 128, "i8s") == 1 and kind(small, 4, "i8s") == 1 and kind(small, 4, "f16") == 1
+    assert B.cmn_plan_step_kernel_kind(B.Plan(small, 4, 4).h, 0, B.CMN_MEAN_TO_ALL_REPLICAS) == 1
+    assert B.cmn_plan_step_kernel_kind(B.Plan(small, 4, 4).h, 0, B.CMN_MEAN_TO_MEAN_GRADS) == 3
     assert B.cmn_plan_step_kernel_kind(None) == -1
     # a launch over few tiles takes the one-pass kernel whatever the plan-wide rule says, and the
     # query reports it: whole small lists, and small layer groups of a large list
