@@ -231,3 +231,32 @@ def test_config3_resnet50_k32_average_to_all_replicas_full_size():
             assert_bit_equal(a, b, f"replica {k} tensor {t}")
     for t, (a, b) in enumerate(zip(dc.get(dc.p) + dc.get(dc.v), p_o + v_o)):
         assert_bit_equal(a, b, f"state {t}")
+
+
+def test_bench_line_carries_the_contract_fields_and_its_own_parity_check(step_kernel_mode):
+    """bench.py on the small workload: one JSON line on stdout with the contract's fields, the roofline and
+    cpu_baseline objects, and a parity check of the timed entry point against the oracle that came out true."""
+    if step_kernel_mode != "auto":
+        pytest.skip("the benchmark is run once, with the library's own kernel choice")
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--config", "1", "--steps", "5", "--warmup", "2"],
+                       capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline", "parity_checked"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 5 and d["unit"] == "GB/s" and d["dtype"] == "f32" and d["vs_baseline"] is None
+    assert d["config"]["workload"] == "mlp_k2_f32" and d["parity_checked"] is True
+    rf = d["roofline"]
+    assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    assert rf["kernel"] == "k_step_state_first<16,0,0>" and rf["launches_per_step"] == 1 and "traffic" in rf
+    assert rf["cold"]["kernel_us"] > 0 and rf["read_ceiling_GBps"] > 1000 and rf["copy_ceiling_GBps"] > 1000
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["single_thread"]["cores"] == 1
