@@ -119,8 +119,10 @@ def _addr(x) -> Optional[int]:
 
 
 def _ptr_array(ptrs: Optional[Sequence]):
-    if ptrs is None:
-        return None
+    """Host array of addresses for the C side; an array made by an earlier call is passed through, so that a
+    caller in a loop can marshal its tensor lists once."""
+    if ptrs is None or isinstance(ptrs, ctypes.Array):
+        return ptrs
     arr = (ctypes.c_void_p * max(1, len(ptrs)))()
     for i, p in enumerate(ptrs):
         arr[i] = _addr(p)
@@ -134,6 +136,11 @@ def _stream(stream) -> Optional[int]:
     if isinstance(stream, int):
         return stream or None
     return int(stream.cuda_stream)
+
+
+def ptr_array(ptrs: Sequence):
+    """Public form of the marshalling step: tensors / addresses -> a reusable host pointer array."""
+    return _ptr_array(ptrs)
 
 
 # ------------------------------------------------------------------ C entry points, same names

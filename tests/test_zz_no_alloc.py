@@ -132,3 +132,13 @@ def test_captured_into_a_hip_graph_and_replayed_between_eager_calls():
             for t, (x, y) in enumerate(zip(got.get(got.p) + got.get(got.v) + got.get(got.m),
                                            ref.get(ref.p) + ref.get(ref.v) + ref.get(ref.m))):
                 assert_bit_equal(x, y, f"replay {step} {name} tensor {t}")
+
+
+def test_vgg16_list_uses_half_of_the_table_array_full_size():
+    """VGG-16's 135 k tiles need 8.7 MB of the 16 MiB array (about 2,400 table-writing launches on the first call)."""
+    import dataclasses
+    c = dataclasses.replace(wl.config(5), K=2, n_chunks=2, name="vgg16_k2_f32")
+    ref, na, plan = _pair(c)
+    assert 8_000_000 < plan.workspace_bytes < B.CMN_NOALLOC_SCRATCH_BYTES
+    _step_both(c, ref, na, plan, 0, B.CMN_MEAN_NONE)
+    _step_both(c, ref, na, plan, 1, B.CMN_MEAN_TO_MEAN_GRADS)
