@@ -70,8 +70,8 @@ enum cmn_dtype {
 enum cmn_mean_dest {
     CMN_MEAN_NONE = 0,            /* nowhere: only p and the optimizer state are written      */
     CMN_MEAN_TO_MEAN_GRADS = 1,   /* into the bound mean_grad_ptrs (float32)                   */
-    CMN_MEAN_TO_ALL_REPLICAS = 2  /* over every replica's own gradient tensors, i.e. the
-                                     "every worker receives the average" half of an allreduce;
+    CMN_MEAN_TO_ALL_REPLICAS = 2  /* over every replica's own gradient tensors, i.e. the half of
+                                     an allreduce that hands the result to every worker;
                                      rounded to nearest even when gradients are 16-bit        */
 };
 
