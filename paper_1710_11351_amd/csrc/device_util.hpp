@@ -234,16 +234,41 @@ __device__ __forceinline__ void fold_batch(float (&acc)[GradT<DT>::VEC], int j, 
     for (int u = 0; u < B; ++u) G::accumulate(acc, g[u], sc[u]);
 }
 
-// The whole K-term fold: batches of U, then the remainder in halving batches so that a K
-// that is not a multiple of U still keeps several loads in flight.
-template <int DT, int U, typename PtrFn, typename ScaleFn>
+// The last n < B replicas of the order as one batch: the loads that exist are requested together
+// (n is uniform over the workgroup, so the conditions are scalar branches).
+template <int DT, int B, typename PtrFn, typename ScaleFn>
+__device__ __forceinline__ void fold_tail(float (&acc)[GradT<DT>::VEC], int j, int n, PtrFn ptr_of, ScaleFn scale_of) {
+    using G = GradT<DT>;
+    typename G::raw g[B];
+    float sc[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u)
+        if (u < n) {
+            g[u] = load_stream<typename G::raw>(ptr_of(j + u));
+            sc[u] = DT == CMN_I8S ? scale_of(j + u) : 1.0f;
+        }
+#pragma unroll
+    for (int u = 0; u < B; ++u)
+        if (u < n) G::accumulate(acc, g[u], sc[u]);
+}
+
+// The whole K-term fold: batches of U, then the remainder.  ONE_TAIL: the remainder goes out as one batch
+// (what the two-phase kernels want: at two waves per SIMD every extra round trip shows, K = 13: 290 -> 261 us,
+// K = 15: 318 -> 292 us).  Otherwise it goes out in halving batches of 8, 4, 2, 1, which costs the one-pass
+// kernels nothing at their occupancy and keeps their register count (the single batch would raise it by 10-30,
+// for int8 to 256, and slow K = 4 by 3 %).
+template <int DT, int U, bool ONE_TAIL = false, typename PtrFn, typename ScaleFn>
 __device__ __forceinline__ void fold_all(float (&acc)[GradT<DT>::VEC], int K, PtrFn ptr_of, ScaleFn scale_of) {
     int j = 0;
     for (; j + U <= K; j += U) fold_batch<DT, U>(acc, j, ptr_of, scale_of);
-    if (U > 8 && j + 8 <= K) { fold_batch<DT, 8>(acc, j, ptr_of, scale_of); j += 8; }
-    if (U > 4 && j + 4 <= K) { fold_batch<DT, 4>(acc, j, ptr_of, scale_of); j += 4; }
-    if (U > 2 && j + 2 <= K) { fold_batch<DT, 2>(acc, j, ptr_of, scale_of); j += 2; }
-    if (j < K) fold_batch<DT, 1>(acc, j, ptr_of, scale_of);
+    if constexpr (ONE_TAIL) {
+        if (j < K) fold_tail<DT, U>(acc, j, K - j, ptr_of, scale_of);
+    } else {
+        if (U > 8 && j + 8 <= K) { fold_batch<DT, 8>(acc, j, ptr_of, scale_of); j += 8; }
+        if (U > 4 && j + 4 <= K) { fold_batch<DT, 4>(acc, j, ptr_of, scale_of); j += 4; }
+        if (U > 2 && j + 2 <= K) { fold_batch<DT, 2>(acc, j, ptr_of, scale_of); j += 2; }
+        if (j < K) fold_batch<DT, 1>(acc, j, ptr_of, scale_of);
+    }
 }
 
 // Optimizer hyper-parameters as the kernels receive them (by value).

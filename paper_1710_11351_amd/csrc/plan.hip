@@ -144,10 +144,13 @@ int64_t two_phase_grid(const cmn_plan *p) {
 //  - ring reduce: two-phase from 8 replicas on;
 //  - fused step: the stores of p and the optimizer state disturb the gradient reads less while
 //    they end in the 256 MB memory-side cache, so with cache-resident state (ResNet-50 with
-//    MomentumSGD, 204 MB) the one-pass kernel stays ahead until the replicas deliver about 56
-//    bytes per element (fp32: 14 replicas, 16-bit: 28); with state beyond the cache (ResNet-50
-//    with Adam, 306 MB; VGG-16) the two-phase kernel wins from about 32 bytes per element, and
-//    likewise when the average is written back to all K replicas.
+//    MomentumSGD, 204 MB) the one-pass kernel stays ahead until the replicas deliver about 44
+//    bytes per element (fp32: 11 replicas, 16-bit: 22; cache-swept launches, K = 10: 232 vs
+//    235 us, K = 11: 252 vs 244, K = 13: 290 vs 265; the same with Adam, 306 MB: K = 9: 250 vs
+//    260, K = 11: 289 vs 281; 50 M elements, 400 MB: K = 8: 390 vs 408); with state beyond twice
+//    the cache (75 M elements and more, VGG-16) the two-phase kernel wins from about 32 bytes
+//    per element (K = 8: 633 vs 613 us), and likewise when the average is written back to all K
+//    replicas.
 static bool two_phase_possible(const cmn_plan *p) {
     return p->step_mode != STEP_ONE_PASS && p->dtype != CMN_I8S && p->tile_elems == kBlock * vec_elems(p->dtype);
 }
@@ -157,9 +160,9 @@ bool prefer_two_phase_reduce(const cmn_plan *p) {
 bool prefer_two_phase_step(const cmn_plan *p, int state_bytes_per_elem, int mean_dest) {
     if (!two_phase_possible(p)) return false;
     if (p->step_mode == STEP_TWO_PHASE) return true;
-    const bool cached = double(p->N) * state_bytes_per_elem <= 256.0 * 1024.0 * 1024.0;
+    const bool cached = !beyond_cache(double(p->N) * state_bytes_per_elem);
     const bool light_stores = cached && mean_dest != CMN_MEAN_TO_ALL_REPLICAS;
-    return p->K * elem_bytes(p->dtype) >= (light_stores ? 56 : 32);
+    return p->K * elem_bytes(p->dtype) >= (light_stores ? 44 : 32);
 }
 
 // Few fp32 replicas, the average stored at most once, state that stays in the memory-side cache: the one-pass

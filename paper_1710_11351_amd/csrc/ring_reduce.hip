@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_ring_reduce_two_phase(
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[i] = sum_identity();
                 if (e < in_chunk)
-                    fold_all<DT, U>(
+                    fold_all<DT, U, true>(
                         acc, K, [&](int j) { return src + (long long)ring_rank(s, j, K) * L + e; },
                         [&](int j) { return load_uniform(scale_ptrs[ring_rank(s, j, K)] + c); });
 #pragma unroll

@@ -86,7 +86,7 @@ struct TileView {
     // Averaged gradient of the thread's run of VEC elements (vector number vi of the tile): fold of
     // the K replicas, times 1/K, then dealt over the wavefront so that the fp32 side coalesces.
     // Every thread of the workgroup calls this; a thread without a vector contributes zeros.
-    template <int U>
+    template <int U, bool ONE_TAIL = false>
     __device__ __forceinline__ void averaged(f32x4 (&out)[Q], int vi, const float *const *scale_ptrs, int K,
                                              float inv_k, f32x4 *deal_buf) const {
         float gb[VEC];
@@ -96,7 +96,7 @@ struct TileView {
             const unsigned e = unsigned(head + vi * VEC);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) gb[i] = sum_identity();
-            fold_all<DT, U>(
+            fold_all<DT, U, ONE_TAIL>(
                 gb, K, [&](int j) { return static_cast<const elem *>(gcol[ring_rank(s, j, K)]) + e0 + e; },
                 [&](int j) { return load_uniform(scale_ptrs[ring_rank(s, j, K)] + chunk); });
 #pragma unroll
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
             const int ti = tile0 + m * W;
             if (ti < n_tiles) {
                 const TV tv(load_tile(tiles, ti), grad_cols, K);
-                tv.template averaged<U>(gbar[m], int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
+                tv.template averaged<U, true>(gbar[m], int(threadIdx.x), scale_ptrs, K, inv_k, deal_buf);
                 tv.ragged(scale_ptrs, K, inv_k, o);
             }
         }
