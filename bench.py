@@ -55,6 +55,7 @@ def algorithmic_bytes(c, entry="step", mean_dest=0, opt="sgd"):
         "ring_reduce": (K * eg + 4) * N,
         "scale_unpack": 8 * N,
         "momentum_sgd": 20 * N,
+        "adam": 28 * N,
     }[entry]
 
 
@@ -227,7 +228,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = headline)")
-    ap.add_argument("--staged", action="store_true", help="also time the four staged entry points")
+    ap.add_argument("--staged", action="store_true", help="also time the four staged entry points (the optimizer-only one is cmn_adam with --opt adam)")
     ap.add_argument("--mean-dest", type=int, default=0, choices=(0, 1, 2),
                     help="0: mean gradient not stored; 1: stored once; 2: written back to all K replicas")
     ap.add_argument("--grad-dtype", default=None, choices=("f32", "f16", "bf16", "i8s"),
@@ -358,9 +359,10 @@ def main():
     if args.staged:
         packed = torch.empty(c.K * plan.L, dtype=tg, device="cuda")
         reduced = torch.empty(plan.L, dtype=torch.float32, device="cuda")
+        optimizer_only = (("adam", lambda: plan.adam(1e-3, 0.9, 0.999, 1e-8, c.wd, max(1, it[0]))) if adam else
+                          ("momentum_sgd", lambda: plan.momentum_sgd(c.lr, c.mu, c.wd)))
         for name, fn in (("pack", lambda: plan.pack(packed)), ("ring_reduce", lambda: plan.ring_reduce(packed, reduced)),
-                         ("scale_unpack", lambda: plan.scale_unpack(reduced)),
-                         ("momentum_sgd", lambda: plan.momentum_sgd(c.lr, c.mu, c.wd))):
+                         ("scale_unpack", lambda: plan.scale_unpack(reduced)), optimizer_only):
             n = max(5, args.steps // 2)
             us = time_region(torch, fn, n, 2)[0] / n * 1e3
             ab = algorithmic_bytes(c, name)

@@ -321,13 +321,20 @@ __global__ __launch_bounds__(kBlock, 2) void k_step_two_phase(
     }
 }
 
-// Parameters and optimizer state (and, for the optimizer-only kernels, the mean gradient) of a
-// large model cannot stay in the memory-side cache from one kernel to the next: then they are
-// streamed (VGG-16, 1.1-1.7 GB: cmn_momentum_sgd 525 -> 480 us, fused step 1785 -> 1730 us).  A small
-// model's do stay, and streaming them would cost it 8 % (ResNet-50, 306 MB: 77 -> 83 us).
+// Parameters and optimizer state of a large model cannot stay in the memory-side cache from one
+// kernel to the next: then they are streamed (VGG-16, 1.1-1.7 GB: fused step 1785 -> 1730 us,
+// cmn_momentum_sgd 525 -> 480 us).  The write phase of the fused step keeps the cached policy up to
+// twice the cache size (ResNet-50 with Adam, 306 MB: 570 vs 585 us on cache-swept launches).  The
+// optimizer-only kernels, which run behind cmn_scale_unpack and also read the mean gradient, gain
+// from streaming as soon as mean gradient + parameters + state exceed the cache by a quarter
+// (behind a cache sweep and the unpack kernel, cached vs streamed: MomentumSGD 20 M elements, 240 MB:
+// 62 vs 63 us, 32 M, 384 MB: 96 vs 92, 50 M: 166 vs 145; Adam 16 M, 256 MB: 67 vs 70, 25.6 M, 409 MB:
+// 113 vs 110, 50 M: 245 vs 207 us).
 template <int SRC, int OPT>
 inline int stream_state(const cmn_plan *p) {
-    return int(beyond_cache(double(p->N) * ((OPT == OPT_ADAM ? 12.0 : 8.0) + (SRC == SRC_MEAN ? 4.0 : 0.0))));
+    const double state = double(p->N) * (OPT == OPT_ADAM ? 12.0 : 8.0);
+    if (SRC == SRC_MEAN) return int(state + 4.0 * double(p->N) > 1.25 * 256.0 * 1024.0 * 1024.0);
+    return int(beyond_cache(state));
 }
 
 template <int DT, int SRC, int MEAN, int OPT>
